@@ -1,0 +1,128 @@
+/*
+ * cmpz.h -- C ABI of the MI355X activation compressor.
+ *
+ * The library implements, as HIP kernels for gfx950, the compressor the paper
+ * runs on every convolutional layer's activation tensor in the forward pass and
+ * the decompressor it runs when the backward pass reaches that layer
+ * (Section 4.4; data flow of Section 2.1): an SZ-type error-bounded lossy codec
+ * in absolute-error-bound mode (Section 2.2) whose stages are, in the order of
+ * Section 3.1, pre-quantisation of each fp32 value to an integer, a Lorenzo
+ * predictor on the integers, one quantisation code per value (with out-of-range
+ * residuals kept verbatim), and Huffman coding of the codes.
+ *
+ * Conventions
+ *  - "d_" pointers are DEVICE pointers on the context's GPU, "h_" pointers are
+ *    HOST pointers.  `stream` is a hipStream_t passed as void* (NULL = the
+ *    default stream).  No HIP or torch type appears in this interface.
+ *  - The caller owns every buffer it passes.  The context owns only its scratch
+ *    memory, allocated once in cmp_create and sized by cfg.max_numel; compress
+ *    and decompress allocate nothing and do not synchronise unless stated.
+ *  - All work of one context must be issued on one stream at a time; calls on
+ *    one context are not re-entrant.  Use one context per concurrent stream.
+ *  - Tensors are fp32, contiguous NCHW; d_x, d_xout and d_out must be 16-byte
+ *    aligned.  numel must be below 2^32.  A dimension may be 0 (empty tensor).
+ *  - Return value: 0 = CMP_OK, negative = error, positive = warning.
+ *    Conditions only the GPU can see (container too small, malformed container,
+ *    out-of-range input) are recorded on the device and reported by the next
+ *    synchronising call (cmp_compress with h_size != NULL, cmp_compressed_size,
+ *    cmp_last_status).  The library never aborts and never prints.
+ *  - Same input bytes, error bound and configuration give the same container
+ *    bytes on every run.
+ *
+ * Arithmetic (all fp32, IEEE round-to-nearest-even, no fused multiply-add):
+ *    eb_in = eb - eb * 2^-guard_shift;  s = 2 * eb_in;  r = 1 / s   (host)
+ *    q  = rint(x * r) clamped to [-16384, 16384], NaN -> 0           (compress)
+ *    x' = (float)q * s                                               (decompress)
+ * so that |x - x'| <= eb for every element whose |x * r| <= 16384.
+ */
+#ifndef CMPZ_H
+#define CMPZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CMP_OK           0
+#define CMP_E_ARG      (-1)  /* NULL pointer, bad shape, numel >= 2^32 or > max_numel, eb not
+                                finite or outside [2^-60, 2^60], unsupported configuration   */
+#define CMP_E_NOSPACE  (-2)  /* out_cap smaller than the container; nothing is written past
+                                out_cap and header.status is set when the header fits        */
+#define CMP_E_FORMAT   (-3)  /* decompress: not a container, damaged, or truncated            */
+#define CMP_E_MISMATCH (-4)  /* decompress: shape / eb / configuration differ from the header */
+#define CMP_E_HIP      (-5)  /* a HIP runtime call failed                                     */
+#define CMP_W_RANGE      1   /* some |x*r| > 16384 or non-finite x: those elements were
+                                clamped (NaN -> 0) and the error bound does not hold for them */
+
+typedef struct cmp_ctx cmp_ctx;   /* opaque */
+
+typedef struct {
+    uint32_t radius;       /* residuals d with |d| < radius get symbol d+radius; 1..512        */
+    uint32_t chunk;        /* codes per independently addressable Huffman chunk; 4096          */
+    uint32_t sub;          /* codes per sub-block whose bit count is stored: 32, 64, 128, 256  */
+    uint32_t guard_shift;  /* 1..23, see "Arithmetic" above                                    */
+    uint64_t max_numel;    /* largest tensor this context will be asked to handle              */
+} cmp_config;
+
+/* Defaults: radius 512, chunk 4096, sub 128, guard_shift 7, max_numel 2^28. */
+void cmp_default_config(cmp_config *cfg);
+
+/* Create a context on GPU `device` and allocate its scratch (about
+ * 2 bytes * max_numel + 16 bytes per chunk).  cfg == NULL means defaults. */
+int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device);
+void cmp_destroy(cmp_ctx *ctx);
+
+/* Worst-case container size in bytes for a tensor of this shape (0 on bad
+ * arguments).  A container never exceeds it. */
+size_t cmp_bound(const cmp_ctx *ctx, const int64_t shape[4]);
+
+/* Forward pass (Section 4.4): compress d_x (fp32, shape N,C,H,W) under the
+ * absolute error bound eb into the container at d_out (capacity out_cap bytes).
+ * Stages, each a kernel on `stream`: pre-quantisation, per-(n,c)-plane 2D
+ * Lorenzo prediction, quantisation-code / outlier split and histogram
+ * (Section 3.1); Huffman codebook; chunked bit-packing.
+ * h_size == NULL: fully asynchronous.  h_size != NULL: waits for the stream and
+ * stores the container size; the return value then also reports CMP_E_NOSPACE
+ * (h_size = bytes needed) and CMP_W_RANGE. */
+int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb,
+                 void *d_out, size_t out_cap, size_t *h_size, void *stream);
+
+/* Waits for `stream`, reads the header of a container produced by cmp_compress
+ * and stores its size in bytes (the compression-ratio monitor of Section 4.4
+ * reads this).  Returns CMP_E_NOSPACE (h_size = bytes needed) if that compress
+ * ran out of room, CMP_W_RANGE if it clamped values, CMP_E_FORMAT if d_buf does
+ * not start with a container header. */
+int cmp_compressed_size(cmp_ctx *ctx, const void *d_buf, size_t *h_size, void *stream);
+
+/* Backward pass (Section 4.4): decode the container at d_buf (`size` = bytes
+ * available there), undo the Lorenzo predictor by per-plane 2D prefix sums and
+ * de-quantise into d_xout (fp32, shape N,C,H,W).  shape and eb must be those
+ * given to cmp_compress.  Zeros of the original tensor come back as +0.0f and no
+ * value changes sign, so the re-zero filter of Section 4.4 is the identity.
+ * Asynchronous; a malformed or mismatching container leaves d_xout unspecified
+ * (never written out of bounds) and is reported by cmp_last_status. */
+int cmp_decompress(cmp_ctx *ctx, const void *d_buf, size_t size, const int64_t shape[4],
+                   float eb, float *d_xout, void *stream);
+
+/* Waits for `stream` and returns, then clears, the most severe condition the
+ * GPU recorded for this context since the last query: a negative error code, else
+ * CMP_W_RANGE, else CMP_OK. */
+int cmp_last_status(cmp_ctx *ctx, void *stream);
+
+/* Intermediate results of the LAST cmp_compress on this context, for parity
+ * checks.  Stores a device pointer into the context's scratch (valid until the
+ * next call on the context) and its size in bytes.  The caller synchronises. */
+#define CMP_STAGE_QUANT_CODES 0   /* uint16[numel]: symbol per element, 0 = outlier            */
+#define CMP_STAGE_HIST        1   /* uint32[2*radius]: occurrences of each symbol              */
+#define CMP_STAGE_LENS        2   /* uint8[2*radius]: Huffman code length, 0 = unused          */
+#define CMP_STAGE_CODES       3   /* uint64[2*radius]: length << 56 | canonical code           */
+int cmp_debug_stage(cmp_ctx *ctx, int which, const void **d_ptr, size_t *bytes);
+
+const char *cmp_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CMPZ_H */

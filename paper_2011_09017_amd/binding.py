@@ -1,0 +1,201 @@
+"""ctypes binding of libcmpz.so -- argument marshalling only.
+
+The module-level ``cmp_*`` functions mirror include/cmpz.h one to one (raw device
+pointers and sizes).  :class:`Context` is a convenience wrapper that takes torch
+tensors for device memory and the current torch stream; every step of the
+compression path runs in the library's HIP kernels.  There is no fallback: if
+the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcmpz.so")
+
+CMP_OK, CMP_E_ARG, CMP_E_NOSPACE, CMP_E_FORMAT, CMP_E_MISMATCH, CMP_E_HIP, CMP_W_RANGE = 0, -1, -2, -3, -4, -5, 1
+CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES = 0, 1, 2, 3
+
+EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
+           "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror"]
+
+
+class cmp_config(C.Structure):
+    _fields_ = [("radius", C.c_uint32), ("chunk", C.c_uint32), ("sub", C.c_uint32),
+                ("guard_shift", C.c_uint32), ("max_numel", C.c_uint64)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libcmpz.so (built in-tree by ``python -m paper_2011_09017_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2011_09017_amd.build` "
+                "(there is no CPU or PyTorch fallback for the compression path)")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int
+        L.cmp_default_config.argtypes = [vp]; L.cmp_default_config.restype = None
+        L.cmp_create.argtypes = [vp, vp, i32]; L.cmp_create.restype = i32
+        L.cmp_destroy.argtypes = [vp]; L.cmp_destroy.restype = None
+        L.cmp_bound.argtypes = [vp, vp]; L.cmp_bound.restype = sz
+        L.cmp_compress.argtypes = [vp, vp, vp, C.c_float, vp, sz, vp, vp]; L.cmp_compress.restype = i32
+        L.cmp_compressed_size.argtypes = [vp, vp, vp, vp]; L.cmp_compressed_size.restype = i32
+        L.cmp_decompress.argtypes = [vp, vp, sz, vp, C.c_float, vp, vp]; L.cmp_decompress.restype = i32
+        L.cmp_last_status.argtypes = [vp, vp]; L.cmp_last_status.restype = i32
+        L.cmp_debug_stage.argtypes = [vp, i32, vp, vp]; L.cmp_debug_stage.restype = i32
+        L.cmp_strerror.argtypes = [i32]; L.cmp_strerror.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _shape4(shape):
+    assert len(shape) == 4
+    return (C.c_int64 * 4)(*[int(v) for v in shape])
+
+
+# --- one-to-one mirrors of the C ABI (raw pointers as ints) -------------------
+def cmp_default_config() -> cmp_config:
+    cfg = cmp_config()
+    lib().cmp_default_config(C.addressof(cfg))
+    return cfg
+
+
+def cmp_create(cfg: cmp_config | None, device: int):
+    h = C.c_void_p(0)
+    rc = lib().cmp_create(C.addressof(h), C.addressof(cfg) if cfg is not None else None, device)
+    return rc, h.value
+
+
+def cmp_destroy(ctx) -> None:
+    lib().cmp_destroy(ctx)
+
+
+def cmp_bound(ctx, shape) -> int:
+    s = _shape4(shape)
+    return int(lib().cmp_bound(ctx, C.addressof(s)))
+
+
+def cmp_compress(ctx, d_x: int, shape, eb: float, d_out: int, out_cap: int, want_size: bool, stream: int):
+    s = _shape4(shape)
+    size = C.c_size_t(0)
+    rc = lib().cmp_compress(ctx, d_x, C.addressof(s), C.c_float(eb), d_out, out_cap,
+                            C.addressof(size) if want_size else None, stream)
+    return rc, int(size.value)
+
+
+def cmp_compressed_size(ctx, d_buf: int, stream: int):
+    size = C.c_size_t(0)
+    rc = lib().cmp_compressed_size(ctx, d_buf, C.addressof(size), stream)
+    return rc, int(size.value)
+
+
+def cmp_decompress(ctx, d_buf: int, size: int, shape, eb: float, d_xout: int, stream: int) -> int:
+    s = _shape4(shape)
+    return lib().cmp_decompress(ctx, d_buf, size, C.addressof(s), C.c_float(eb), d_xout, stream)
+
+
+def cmp_last_status(ctx, stream: int) -> int:
+    return lib().cmp_last_status(ctx, stream)
+
+
+def cmp_debug_stage(ctx, which: int):
+    p = C.c_void_p(0)
+    n = C.c_size_t(0)
+    rc = lib().cmp_debug_stage(ctx, which, C.addressof(p), C.addressof(n))
+    return rc, p.value, int(n.value)
+
+
+def cmp_strerror(code: int) -> str:
+    return lib().cmp_strerror(code).decode()
+
+
+class CmpError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where}: {cmp_strerror(code)} ({code})")
+        self.code = code
+
+
+class Context:
+    """Owns one cmp_ctx.  Tensors supply device memory; the current torch stream is used."""
+
+    def __init__(self, radius=512, chunk=4096, sub=128, guard_shift=7, max_numel=1 << 28, device=0):
+        cfg = cmp_config(radius, chunk, sub, guard_shift, max_numel)
+        rc, self._h = cmp_create(cfg, device)
+        if rc != CMP_OK:
+            self._h = None
+            raise CmpError(rc, "cmp_create")
+        self.cfg = cfg
+        self.device = torch.device("cuda", device)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            cmp_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def _stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def bound(self, shape) -> int:
+        return cmp_bound(self._h, shape)
+
+    def compress(self, x: torch.Tensor, eb: float, out: torch.Tensor | None = None, sync: bool = True):
+        """Returns (container tensor (uint8, full capacity), size or None, rc)."""
+        assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 4
+        if out is None:
+            out = torch.empty(self.bound(x.shape), dtype=torch.uint8, device=x.device)
+        rc, size = cmp_compress(self._h, x.data_ptr(), x.shape, eb, out.data_ptr(), out.numel(), sync,
+                                self._stream())
+        if rc < 0 and rc != CMP_E_NOSPACE:
+            raise CmpError(rc, "cmp_compress")
+        return out, (size if sync else None), rc
+
+    def compressed_size(self, buf: torch.Tensor):
+        return cmp_compressed_size(self._h, buf.data_ptr(), self._stream())
+
+    def decompress(self, buf: torch.Tensor, size: int, shape, eb: float, out: torch.Tensor | None = None):
+        assert buf.is_cuda and buf.dtype == torch.uint8
+        if out is None:
+            out = torch.empty(tuple(shape), dtype=torch.float32, device=buf.device)
+        rc = cmp_decompress(self._h, buf.data_ptr(), size, shape, eb, out.data_ptr(), self._stream())
+        if rc != CMP_OK:
+            raise CmpError(rc, "cmp_decompress")
+        return out
+
+    def last_status(self) -> int:
+        return cmp_last_status(self._h, self._stream())
+
+    def stage(self, which: int) -> torch.Tensor:
+        """Copy of an intermediate result of the last compress (uint8 tensor on the host)."""
+        rc, ptr, nbytes = cmp_debug_stage(self._h, which)
+        if rc != CMP_OK:
+            raise CmpError(rc, "cmp_debug_stage")
+        torch.cuda.synchronize(self.device)
+        host = torch.empty(nbytes, dtype=torch.uint8)
+        if nbytes:
+            hip = _hip()
+            err = hip.hipMemcpy(C.c_void_p(host.data_ptr()), C.c_void_p(ptr), C.c_size_t(nbytes), 2)
+            if err != 0:
+                raise RuntimeError(f"hipMemcpy failed: {err}")
+        return host
+
+
+_hiprt = None
+
+
+def _hip():
+    global _hiprt
+    if _hiprt is None:
+        _hiprt = C.CDLL("libamdhip64.so")
+        _hiprt.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        _hiprt.hipMemcpy.restype = C.c_int
+    return _hiprt

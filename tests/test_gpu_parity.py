@@ -1,0 +1,252 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: bit-exact for symbols, histogram, code lengths, codes, the whole container
+and the reconstructed fp32 values; |x - x'| <= eb on every element (Section 2.2);
+zeros stay zero (Sections 3.2, 4.4).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2011_09017_amd.workloads import WORKLOADS, activation
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2011_09017_amd import binding
+    binding.lib()
+    return binding
+
+
+def make_ctx(gpu, **kw):
+    kw.setdefault("max_numel", 1 << 22)
+    return gpu.Context(**kw)
+
+
+def check_case(gpu, orc, x_host: np.ndarray, eb: float, ctx, ocfg, stages=True, expect_rc=0):
+    """Compress on both sides, compare everything, decompress on both sides, compare."""
+    shape = x_host.shape
+    x = torch.from_numpy(x_host).cuda()
+    buf, size, rc = ctx.compress(x, eb)
+    assert rc == expect_rc, gpu.cmp_strerror(rc)
+    orc_rc, obuf, osize, ost = orc.compress(x_host, eb, ocfg, want_stages=True)
+    assert orc_rc == expect_rc
+    if stages:
+        sym = ctx.stage(gpu.CMP_STAGE_QUANT_CODES).numpy().view(np.uint16)
+        assert np.array_equal(sym, ost.sym), "quant codes differ"
+        hist = ctx.stage(gpu.CMP_STAGE_HIST).numpy().view(np.uint32)
+        assert np.array_equal(hist, ost.cnt), "histogram differs"
+        lens = ctx.stage(gpu.CMP_STAGE_LENS).numpy()
+        assert np.array_equal(lens, ost.lens), "code lengths differ"
+        codes = ctx.stage(gpu.CMP_STAGE_CODES).numpy().view(np.uint64)
+        assert np.array_equal(codes & np.uint64((1 << 56) - 1), ost.codes), "codes differ"
+        assert np.array_equal((codes >> np.uint64(56)).astype(np.uint8), ost.lens)
+    assert size == osize, (size, osize)
+    got = buf[:size].cpu().numpy()
+    if not np.array_equal(got, obuf):
+        bad = np.nonzero(got != obuf)[0]
+        h = orc.parse_header(obuf)
+        raise AssertionError(f"container differs at {bad.size} bytes, first {bad[:8]}, header {h}")
+    # outlier lists sit inside the container; decode them for an explicit comparison
+    h = orc.parse_header(got)
+    oi = got[h["off_outl_idx"]:h["off_outl_idx"] + 4 * h["n_outliers"]].view("<u4")
+    ov = got[h["off_outl_val"]:h["off_outl_val"] + 4 * h["n_outliers"]].view("<i4")
+    assert np.array_equal(oi, ost.outl_idx) and np.array_equal(ov, ost.outl_val)
+    # decompress
+    y = ctx.decompress(buf, size, shape, eb)
+    assert ctx.last_status() in (0, gpu.CMP_W_RANGE)
+    orc_rc, oy = orc.decompress(obuf, shape, eb, ocfg)
+    assert orc_rc == 0
+    yh = y.cpu().numpy()
+    assert np.array_equal(yh.view(np.uint32), oy.view(np.uint32)), "reconstruction differs"
+    ok = np.isfinite(x_host) if expect_rc else np.ones(shape, bool)
+    if expect_rc == 0:
+        assert np.abs(yh.astype(np.float64) - x_host.astype(np.float64)).max(initial=0) <= float(np.float32(eb))
+    assert np.all(yh[(x_host == 0) & ok].view(np.uint32) == 0)
+    return h
+
+
+SMALL = [
+    # shape, k, p_zero, eb
+    ((1, 64, 56, 56), 5, 0.5, 1e-2),        # configs[0]
+    ((2, 3, 7, 7), 5, 0.5, 1e-2),
+    ((3, 5, 55, 55), 5, 0.5, 1e-3),
+    ((1, 2, 224, 224), 5, 0.5, 1e-2),
+    ((2, 2, 14, 14), 5, 0.85, 1e-2),
+    ((1, 1, 1, 4099), 5, 0.5, 1e-2),
+    ((1, 1, 4099, 1), 5, 0.5, 1e-2),
+    ((1, 1, 1, 2), 5, 0.5, 1e-2),
+    ((7, 1, 1, 1), 5, 0.5, 1e-2),
+    ((1, 3, 33, 19), 3, 0.6, 5e-3),
+    ((2, 8, 28, 28), 5, 0.5, 1e-1),
+    ((1, 1, 300, 1000), 5, 0.5, 1e-2),
+    ((5, 7, 13, 3), 3, 0.5, 5e-4),
+]
+
+
+@pytest.mark.parametrize("shape,k,p_zero,eb", SMALL)
+def test_small_cases_bit_exact(gpu, orc, shape, k, p_zero, eb):
+    ctx = make_ctx(gpu)
+    x = activation(shape, k, p_zero, seed=sum(shape)).numpy()
+    check_case(gpu, orc, x, eb, ctx, orc.Config())
+
+
+@pytest.mark.parametrize("sub", [32, 64, 128])
+@pytest.mark.parametrize("radius", [512, 16, 1])
+def test_sub_and_radius_variants(gpu, orc, sub, radius):
+    ctx = make_ctx(gpu, sub=sub, radius=radius)
+    x = activation((2, 3, 55, 55), 5, 0.5, seed=sub + radius).numpy()
+    h = check_case(gpu, orc, x, 1e-3, ctx, orc.Config(radius=radius, sub=sub))
+    if radius < 512:
+        assert h["n_outliers"] > 0
+
+
+def test_all_zero_constant_and_single_symbol(gpu, orc):
+    ctx = make_ctx(gpu)
+    x = np.zeros((2, 2, 30, 30), np.float32)
+    h = check_case(gpu, orc, x, 1e-2, ctx, orc.Config())
+    assert h["max_len"] == 1
+    x[:] = 3.25
+    check_case(gpu, orc, x, 1e-2, ctx, orc.Config())
+
+
+def test_empty_tensor(gpu, orc):
+    ctx = make_ctx(gpu)
+    for shape in [(0, 3, 5, 5), (2, 3, 0, 5)]:
+        x = np.zeros(shape, np.float32)
+        check_case(gpu, orc, x, 1e-2, ctx, orc.Config(), stages=False)
+
+
+def test_adversarial_values(gpu, orc):
+    """Quantiser midpoints, +-0, denormals, the edge of the range, every element an outlier."""
+    ctx = make_ctx(gpu)
+    _, _, s, r = orc.constants(1e-2)
+    k = np.arange(0, 16385, dtype=np.float64)
+    v = np.concatenate([(k + 0.5) * float(s), k * float(s)]).astype(np.float32)
+    v = np.concatenate([v, np.nextafter(v, np.float32(np.inf)), np.nextafter(v, np.float32(-np.inf))])
+    v = np.concatenate([v, -v, np.array([0.0, -0.0, 1e-45, -1e-45, 1e-39], np.float32)])
+    v = v[np.abs(v * r) <= np.float32(16384.0)]
+    rng = np.random.default_rng(0)
+    rng.shuffle(v)
+    n = (v.size // (4 * 37 * 41)) * (4 * 37 * 41)
+    x = v[:n].reshape(4, -1, 37, 41)
+    h = check_case(gpu, orc, x, 1e-2, ctx, orc.Config())
+    assert h["n_outliers"] > n // 2
+
+
+def test_nan_inf_out_of_range(gpu, orc):
+    ctx = make_ctx(gpu)
+    x = activation((1, 4, 40, 40), seed=3).numpy()
+    x[0, 0, 3, 3] = np.inf; x[0, 1, 7, 0] = -np.inf; x[0, 2, 0, 0] = np.nan; x[0, 3, 39, 39] = 1e30
+    h = check_case(gpu, orc, x, 1e-2, ctx, orc.Config(), expect_rc=gpu.CMP_W_RANGE)
+    assert h["range_events"] == 4
+
+
+def test_nospace_and_argument_errors(gpu, orc):
+    ctx = make_ctx(gpu)
+    x = torch.from_numpy(activation((1, 4, 40, 40), seed=4).numpy()).cuda()
+    buf, size, rc = ctx.compress(x, 1e-2)
+    assert rc == 0
+    small = torch.zeros(size - 16, dtype=torch.uint8, device="cuda")
+    guard = torch.full((4096,), 0xAB, dtype=torch.uint8, device="cuda")
+    _, need, rc = ctx.compress(x, 1e-2, out=small)
+    assert rc == gpu.CMP_E_NOSPACE and need == size
+    assert ctx.last_status() == gpu.CMP_E_NOSPACE and ctx.last_status() == 0
+    assert bool((guard == 0xAB).all())
+    tiny = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    _, _, rc = ctx.compress(x, 1e-2, out=tiny)
+    assert rc == gpu.CMP_E_NOSPACE
+    for bad_eb in [0.0, -1.0, float("nan"), float("inf"), 2.0 ** -61]:
+        with pytest.raises(gpu.CmpError):
+            ctx.compress(x, bad_eb)
+    with pytest.raises(gpu.CmpError):
+        gpu.Context(radius=513)
+    with pytest.raises(gpu.CmpError):
+        gpu.Context(sub=100)
+    big = torch.zeros((1, 1, 2048, 4096), device="cuda")
+    with pytest.raises(gpu.CmpError):
+        make_ctx(gpu, max_numel=1 << 20).compress(big, 1e-2)
+
+
+def test_corrupted_containers_are_rejected(gpu, orc):
+    ctx = make_ctx(gpu)
+    shape = (1, 2, 30, 30)
+    xh = activation(shape, seed=9).numpy()
+    xh[0, 0, 4, 4] = 200.0
+    x = torch.from_numpy(xh).cuda()
+    buf, size, rc = ctx.compress(x, 1e-2)
+    good = buf[:size].clone()
+    fields = [k for k in orc.HDR if k not in ("range_events", "total_bits")]
+    for name in fields + ["tail"]:
+        bad = good.clone()
+        o = 255 if name == "tail" else orc.HDR[name]
+        bad[o] ^= 1
+        ctx.decompress(bad, size, shape, 1e-2)
+        st = ctx.last_status()
+        host_rc, _ = orc.decompress(bad.cpu().numpy(), shape, 1e-2)
+        assert st in (gpu.CMP_E_FORMAT, gpu.CMP_E_MISMATCH), name
+        assert st == host_rc, (name, st, host_rc)
+    # caller-side mismatches
+    ctx.decompress(good, size, shape, 2e-2); assert ctx.last_status() == gpu.CMP_E_MISMATCH
+    ctx.decompress(good, size, (1, 2, 30, 31), 1e-2); assert ctx.last_status() in (gpu.CMP_E_MISMATCH, gpu.CMP_E_FORMAT)
+    ctx.decompress(good, size - 16, shape, 1e-2); assert ctx.last_status() == gpu.CMP_E_FORMAT
+    with pytest.raises(gpu.CmpError):
+        ctx.decompress(good, 100, shape, 1e-2)
+    # damaged body: must not crash, and a clean call afterwards still works
+    rng = np.random.default_rng(1)
+    h = orc.parse_header(good.cpu().numpy())
+    for sect in ["off_lens", "off_chunk_off", "off_sub_bits", "off_payload", "off_outl_idx"]:
+        bad = good.clone()
+        bad[h[sect] + int(rng.integers(0, 8))] ^= 0x10
+        ctx.decompress(bad, size, shape, 1e-2)
+        ctx.last_status()
+    y = ctx.decompress(good, size, shape, 1e-2)
+    assert ctx.last_status() == 0
+    assert np.abs(y.cpu().numpy() - xh).max() <= 1e-2
+
+
+def test_determinism_and_context_reuse(gpu, orc):
+    ctx = make_ctx(gpu)
+    a = torch.from_numpy(activation((2, 4, 56, 56), seed=1).numpy()).cuda()
+    b = torch.from_numpy(activation((1, 3, 28, 28), seed=2).numpy()).cuda()
+    ba, sa, _ = ctx.compress(a, 1e-2)
+    ref = ba[:sa].clone()
+    for _ in range(3):
+        bb, sb, _ = ctx.compress(b, 5e-3)
+        ba2, sa2, _ = ctx.compress(a, 1e-2)
+        assert sa2 == sa and torch.equal(ba2[:sa2], ref)
+    # recompressing the reconstruction reproduces the same codes (quantiser fixed point)
+    y = ctx.decompress(ba, sa, a.shape, 1e-2)
+    by, sy, _ = ctx.compress(y, 1e-2)
+    y2 = ctx.decompress(by, sy, a.shape, 1e-2)
+    assert torch.equal(y.view(torch.int32), y2.view(torch.int32))
+
+
+FULL = [("cfg2_vgg16_conv1_2", 0), ("cfg3_resnet50_bottleneck", 0), ("cfg4_alexnet_conv1", 0)]
+
+
+@pytest.mark.parametrize("name,ti", FULL)
+def test_full_size_configs_bit_exact(gpu, orc, name, ti):
+    """BASELINE configs 2-4 at full size: whole container and whole reconstruction, byte for byte."""
+    wl = WORKLOADS[name]
+    ctx = make_ctx(gpu, max_numel=wl.numel())
+    x = wl.tensor(ti, device="cuda")
+    xh = x.cpu().numpy()
+    for eb in wl.ebs:
+        print(f"[parity] {name} eb={eb} numel={xh.size}", flush=True)
+        buf, size, rc = ctx.compress(x, eb)
+        assert rc == 0
+        orc_rc, obuf, osize, _ = orc.compress(xh, eb)
+        assert orc_rc == 0 and size == osize
+        assert np.array_equal(buf[:size].cpu().numpy(), obuf)
+        y = ctx.decompress(buf, size, x.shape, eb)
+        assert ctx.last_status() == 0
+        yh = y.cpu().numpy()
+        orc_rc, oy = orc.decompress(obuf, xh.shape, eb)
+        assert orc_rc == 0 and np.array_equal(yh.view(np.uint32), oy.view(np.uint32))
+        assert np.abs(yh.astype(np.float64) - xh.astype(np.float64)).max() <= float(np.float32(eb))
+        assert np.all(yh[xh == 0].view(np.uint32) == 0)
+        print(f"[parity] ok ratio={xh.nbytes / size:.3f}", flush=True)
