@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the compression hot path on one MI355X.
+
+A step = one pass of the whole path over one batch of synthetic activations:
+every tensor of the workload is compressed in forward order, then every
+container is decompressed in reverse order, all on one stream (the forward /
+backward pattern of Section 4.4 of the paper).  Inputs are resident in HBM
+before the timed region starts.  Prints ONE JSON line.
+
+  value      = fp32 bytes compressed + fp32 bytes decompressed, per second (GB/s)
+  roofline   = the kernel with the largest share of the step: its algorithmic
+               HBM bytes per second against the 8 TB/s peak, durations measured
+               with HIP events around each of its launches (a second pass over
+               the same steps, so that the events do not perturb `value`)
+  cpu_baseline = the CPU oracle, one core, on a bounded sample of the workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# Algorithmic HBM bytes per element of each kernel (cbar = compressed bytes per element,
+# measured): what the kernel must read and write once if nothing is re-read.
+KERNEL_BYTES = {
+    "k_quant_lorenzo_split_hist": lambda cbar: 4.0 + 2.0,      # read x, write u16 symbols
+    "k_chunk_bits": lambda cbar: 2.0,                          # read symbols
+    "k_encode": lambda cbar: 2.0 + cbar,                       # read symbols, write payload
+    "k_decode": lambda cbar: cbar + 4.0,                       # read payload, write int32 residuals
+    "k_row_scan": lambda cbar: 8.0,
+    "k_col_scan_dequant": lambda cbar: 8.0,
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5_resnet18_stream")
+    ap.add_argument("--eb", type=float, default=None)
+    ap.add_argument("--sub", type=int, default=128)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=2, help="tensors of the workload the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build targets one GPU; the path shards with no communication "
+              "(see DESIGN.md), so only --gpus 1 is measured", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2011_09017_amd import binding
+    from paper_2011_09017_amd.workloads import WORKLOADS
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    binding.lib()                                    # fails loudly if libcmpz.so is missing
+    wl = WORKLOADS[args.workload]
+    eb = args.eb if args.eb is not None else wl.ebs[0]
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+
+    xs = [wl.tensor(i, device=dev) for i in range(len(wl.shapes))]
+    numels = [x.numel() for x in xs]
+    total = sum(numels)
+    ctx = binding.Context(sub=args.sub, max_numel=max(numels))
+    bounds = [ctx.bound(x.shape) for x in xs]
+    arena = [torch.empty(b, dtype=torch.uint8, device=dev) for b in bounds]
+    outs = [torch.empty_like(x) for x in xs]
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    h = ctx._h
+
+    def compress_all():
+        for x, buf in zip(xs, arena):
+            rc, _ = binding.cmp_compress(h, x.data_ptr(), x.shape, eb, buf.data_ptr(), buf.numel(), False, stream)
+            assert rc == 0, binding.cmp_strerror(rc)
+
+    def decompress_all():
+        for x, buf, out, cap in zip(reversed(xs), reversed(arena), reversed(outs), reversed(bounds)):
+            rc = binding.cmp_decompress(h, buf.data_ptr(), cap, x.shape, eb, out.data_ptr(), stream)
+            assert rc == 0, binding.cmp_strerror(rc)
+
+    def step():
+        compress_all()
+        decompress_all()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    st = ctx.last_status()
+    assert st == 0, binding.cmp_strerror(st)
+    sizes = []
+    for buf in arena:
+        rc, size = ctx.compressed_size(buf)
+        assert rc == 0
+        sizes.append(size)
+    comp_bytes = sum(sizes)
+    cbar = comp_bytes / total
+
+    # correctness gate inside the bench: the error bound on the last warm-up pass
+    worst = 0.0
+    for x, out in zip(xs, outs):
+        worst = max(worst, float((x.double() - out.double()).abs().max()))
+    assert worst <= float(torch.tensor(eb, dtype=torch.float32)), worst
+
+    # ---- timed region: exactly K steps -------------------------------------------------
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # per-phase times with events on the same stream
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    tc = td = 0.0
+    for _ in range(args.steps):
+        e[0].record(); compress_all(); e[1].record(); decompress_all(); e[2].record()
+        torch.cuda.synchronize()
+        tc += e[0].elapsed_time(e[1]); td += e[1].elapsed_time(e[2])
+    tc /= args.steps; td /= args.steps
+
+    # ---- per-kernel durations (events around every launch), same K steps ----------------
+    ctx.profile(True)
+    for _ in range(args.steps):
+        step()
+    prof = ctx.profile_read()
+    ctx.profile(False)
+    kern = {}
+    for name, (ms, launches) in prof.items():
+        kern[name] = {"ms_per_step": ms / args.steps, "launches_per_step": launches // args.steps,
+                      "avg_us": 1e3 * ms / launches}
+    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    bytes_fn = KERNEL_BYTES.get(dom)
+    roofline = None
+    if bytes_fn is not None:
+        alg_bytes_step = bytes_fn(cbar) * total                 # over all launches of one step
+        achieved = alg_bytes_step / (kern[dom]["ms_per_step"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "alg_bytes_per_elem": round(bytes_fn(cbar), 4),
+                    "avg_launch_us": round(kern[dom]["avg_us"], 2),
+                    "launches_per_step": kern[dom]["launches_per_step"]}
+
+    value = 2 * 4.0 * total / (ms_per_step * 1e-3) / 1e9
+    alg_roundtrip = (12.0 + 2 * cbar) * total                  # 8 + cbar compress, 4 + cbar decompress
+    result = {
+        "metric": "compress+decompress GB/s of fp32 activations (frac. of HBM peak); compression ratio",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32 quantiser, i32/bit codec", "data": "synthetic",
+        "config": {"workload": wl.name, "tensors": len(xs), "numel": total, "eb": eb, "radius": 512,
+                   "chunk": 4096, "sub": args.sub, "p_zero": wl.p_zero, "box_k": wl.k,
+                   "seed_base": wl.seed(0)},
+        "compression_ratio": round(4.0 * total / comp_bytes, 4),
+        "compressed_bytes_held": comp_bytes,
+        "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
+        "compress_GBps": round(4.0 * total / (tc * 1e-3) / 1e9, 2),
+        "decompress_GBps": round(4.0 * total / (td * 1e-3) / 1e9, 2),
+        "hbm_frac_algorithmic": round(alg_roundtrip / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "max_abs_err": worst,
+        "kernels": {k: {kk: round(vv, 3) for kk, vv in v.items()} for k, v in kern.items()},
+        "roofline": roofline,
+    }
+
+    # ---- CPU baseline: the oracle as it stands, one core, bounded sample ------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        n_s, t_c, t_d = 0, 0.0, 0.0
+        for i in range(min(args.cpu_sample, len(xs))):
+            xh = xs[i].cpu().numpy()
+            a = time.perf_counter()
+            rc, obuf, osize, _ = oracle.compress(xh, eb, oracle.Config(sub=args.sub))
+            b = time.perf_counter()
+            rc2, oy = oracle.decompress(obuf, xh.shape, eb, oracle.Config(sub=args.sub))
+            c = time.perf_counter()
+            assert rc == 0 and rc2 == 0
+            n_s += xh.size; t_c += b - a; t_d += c - b
+        result["cpu_baseline"] = {
+            "value": round(2 * 4.0 * n_s / (t_c + t_d) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {min(args.cpu_sample, len(xs))} tensors of {wl.name} ({n_s} elements), "
+                      f"compress {t_c:.2f} s + decompress {t_d:.2f} s, host has {os.cpu_count()} cpus"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

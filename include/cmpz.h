@@ -61,7 +61,7 @@ typedef struct cmp_ctx cmp_ctx;   /* opaque */
 typedef struct {
     uint32_t radius;       /* residuals d with |d| < radius get symbol d+radius; 1..512        */
     uint32_t chunk;        /* codes per independently addressable Huffman chunk; 4096          */
-    uint32_t sub;          /* codes per sub-block whose bit count is stored: 32, 64, 128, 256  */
+    uint32_t sub;          /* codes per sub-block whose bit count is stored: 32, 64 or 128    */
     uint32_t guard_shift;  /* 1..23, see "Arithmetic" above                                    */
     uint64_t max_numel;    /* largest tensor this context will be asked to handle              */
 } cmp_config;
@@ -119,6 +119,17 @@ int cmp_last_status(cmp_ctx *ctx, void *stream);
 #define CMP_STAGE_LENS        2   /* uint8[2*radius]: Huffman code length, 0 = unused          */
 #define CMP_STAGE_CODES       3   /* uint64[2*radius]: length << 56 | canonical code           */
 int cmp_debug_stage(cmp_ctx *ctx, int which, const void **d_ptr, size_t *bytes);
+
+/* Per-kernel timing for benchmarks.  cmp_profile(ctx, 1) clears the record and makes
+ * every later kernel launch of this context be bracketed by two events on its stream
+ * (this costs time: do not enable it inside a region whose wall time is reported);
+ * cmp_profile(ctx, 0) stops recording.  cmp_profile_read waits for `stream`, then stores,
+ * for up to `cap` kernels, the kernel name (static string), the summed duration in
+ * milliseconds and the number of launches; it returns the number of kernels seen
+ * (which may exceed cap) or a negative error.  Event creation allocates. */
+int cmp_profile(cmp_ctx *ctx, int enable);
+int cmp_profile_read(cmp_ctx *ctx, void *stream, int cap, const char **h_names,
+                     double *h_total_ms, uint64_t *h_launches);
 
 const char *cmp_strerror(int code);
 

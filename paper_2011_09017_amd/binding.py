@@ -20,7 +20,8 @@ CMP_OK, CMP_E_ARG, CMP_E_NOSPACE, CMP_E_FORMAT, CMP_E_MISMATCH, CMP_E_HIP, CMP_W
 CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES = 0, 1, 2, 3
 
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
-           "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror"]
+           "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",
+           "cmp_profile", "cmp_profile_read"]
 
 
 class cmp_config(C.Structure):
@@ -51,6 +52,8 @@ def lib() -> C.CDLL:
         L.cmp_last_status.argtypes = [vp, vp]; L.cmp_last_status.restype = i32
         L.cmp_debug_stage.argtypes = [vp, i32, vp, vp]; L.cmp_debug_stage.restype = i32
         L.cmp_strerror.argtypes = [i32]; L.cmp_strerror.restype = C.c_char_p
+        L.cmp_profile.argtypes = [vp, i32]; L.cmp_profile.restype = i32
+        L.cmp_profile_read.argtypes = [vp, vp, i32, vp, vp, vp]; L.cmp_profile_read.restype = i32
         _lib = L
     return _lib
 
@@ -110,6 +113,20 @@ def cmp_debug_stage(ctx, which: int):
     n = C.c_size_t(0)
     rc = lib().cmp_debug_stage(ctx, which, C.addressof(p), C.addressof(n))
     return rc, p.value, int(n.value)
+
+
+def cmp_profile(ctx, enable: bool) -> int:
+    return lib().cmp_profile(ctx, 1 if enable else 0)
+
+
+def cmp_profile_read(ctx, stream: int, cap: int = 32):
+    names = (C.c_char_p * cap)()
+    ms = (C.c_double * cap)()
+    launches = (C.c_uint64 * cap)()
+    n = lib().cmp_profile_read(ctx, stream, cap, names, ms, launches)
+    if n < 0:
+        return n, {}
+    return n, {names[k].decode(): (float(ms[k]), int(launches[k])) for k in range(min(n, cap))}
 
 
 def cmp_strerror(code: int) -> str:
@@ -173,6 +190,16 @@ class Context:
 
     def last_status(self) -> int:
         return cmp_last_status(self._h, self._stream())
+
+    def profile(self, enable: bool) -> None:
+        cmp_profile(self._h, enable)
+
+    def profile_read(self) -> dict:
+        """{kernel name: (total ms, launches)} since profile(True)."""
+        n, d = cmp_profile_read(self._h, self._stream())
+        if n < 0:
+            raise CmpError(n, "cmp_profile_read")
+        return d
 
     def stage(self, which: int) -> torch.Tensor:
         """Copy of an intermediate result of the last compress (uint8 tensor on the host)."""

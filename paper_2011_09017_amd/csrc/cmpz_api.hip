@@ -9,8 +9,10 @@
 #include <new>
 
 namespace cmpz {
-size_t decode_tables_bytes();
-void launch_decompress_with_tables(const DecompressArgs &a, void *tables, hipStream_t st);
+const char *const kKernelNames[kKernelCount] = {
+    "k_quant_lorenzo_split_hist", "k_codebook", "k_chunk_bits", "k_scan_header", "k_encode", "k_outliers",
+    "k_empty_container", "k_decode_tables", "k_decode", "k_patch_outliers", "k_row_scan",
+    "k_col_scan_dequant"};
 }  // namespace cmpz
 
 using namespace cmpz;
@@ -26,6 +28,7 @@ struct cmp_ctx {
     uint64_t  *d_codes;
     void      *d_tables;
     uint64_t   last_numel;
+    Profiler   prof;
 };
 
 namespace {
@@ -169,6 +172,7 @@ void cmp_destroy(cmp_ctx *ctx)
     if (!ctx) return;
     DeviceGuard guard(ctx->device);
     (void)hipDeviceSynchronize();
+    for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
     (void)hipFree(ctx->d_base);
     delete ctx;
 }
@@ -220,7 +224,7 @@ int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float e
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    launch_compress(a, st);
+    launch_compress(a, &ctx->prof, st);
     ctx->last_numel = numel;
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
     if (h_size) return cmp_compressed_size(ctx, d_out, h_size, stream);
@@ -271,7 +275,7 @@ int cmp_decompress(cmp_ctx *ctx, const void *d_buf, size_t size, const int64_t s
 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
-    launch_decompress_with_tables(a, ctx->d_tables, static_cast<hipStream_t>(stream));
+    launch_decompress(a, ctx->d_tables, &ctx->prof, static_cast<hipStream_t>(stream));
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
     return CMP_OK;
 }
@@ -304,6 +308,38 @@ int cmp_debug_stage(cmp_ctx *ctx, int which, const void **d_ptr, size_t *bytes)
     case CMP_STAGE_CODES: *d_ptr = ctx->d_codes; *bytes = 8 * nsym; return CMP_OK;
     default: return CMP_E_ARG;
     }
+}
+
+int cmp_profile(cmp_ctx *ctx, int enable)
+{
+    if (!ctx) return CMP_E_ARG;
+    ctx->prof.enabled = enable != 0;
+    if (enable) { ctx->prof.recs.clear(); ctx->prof.used = 0; }
+    return CMP_OK;
+}
+
+int cmp_profile_read(cmp_ctx *ctx, void *stream, int cap, const char **names, double *total_ms,
+                     uint64_t *launches)
+{
+    if (!ctx || cap < 0 || (cap > 0 && (!names || !total_ms || !launches))) return CMP_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return CMP_E_HIP;
+    double ms[kKernelCount] = {0};
+    uint64_t cnt[kKernelCount] = {0};
+    for (const Profiler::Rec &r : ctx->prof.recs) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, r.beg, r.end) != hipSuccess) return CMP_E_HIP;
+        ms[r.id] += t;
+        cnt[r.id] += 1;
+    }
+    int n = 0;
+    for (int k = 0; k < kKernelCount; ++k) {
+        if (!cnt[k]) continue;
+        if (n < cap) { names[n] = kKernelNames[k]; total_ms[n] = ms[k]; launches[n] = cnt[k]; }
+        ++n;
+    }
+    return n;
 }
 
 const char *cmp_strerror(int code)

@@ -114,9 +114,9 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
 
 }  // namespace
 
-void launch_codebook(const CompressArgs &a, hipStream_t st)
+void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_codebook, dim3(1), dim3(kCbThreads), 0, st, a);
+    launch(prof, kKCodebook, k_codebook, dim3(1), dim3(kCbThreads), st, a);
 }
 
 }  // namespace cmpz

@@ -8,8 +8,6 @@
 #include "cmpz_internal.h"
 
 namespace cmpz {
-void launch_codebook(const CompressArgs &a, hipStream_t st);   // cmpz_codebook.hip
-
 namespace {
 
 constexpr int kThreads    = 256;
@@ -433,20 +431,20 @@ __global__ void k_empty_container(CompressArgs a)
 
 }  // namespace
 
-void launch_compress(const CompressArgs &a, hipStream_t st)
+void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st)
 {
     if (a.numel == 0) {
-        hipLaunchKernelGGL(k_empty_container, dim3(1), dim3(256), 0, st, a);
+        launch(prof, kKEmpty, k_empty_container, dim3(1), dim3(256), st, a);
         return;
     }
     const uint32_t nchunks = a.lay.nchunks;
     const uint32_t tiles = (nchunks + kTileChunks - 1) / kTileChunks;
-    hipLaunchKernelGGL(k_quant_lorenzo_split_hist, dim3(tiles), dim3(kThreads), 0, st, a);
-    launch_codebook(a, st);
-    hipLaunchKernelGGL(k_chunk_bits, dim3(nchunks), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(k_scan_header, dim3(1), dim3(kScanThreads), 0, st, a);
-    hipLaunchKernelGGL(k_encode, dim3(nchunks), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(k_outliers, dim3(nchunks), dim3(kThreads), 0, st, a);
+    launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist, dim3(tiles), dim3(kThreads), st, a);
+    launch_codebook(a, prof, st);
+    launch(prof, kKChunkBits, k_chunk_bits, dim3(nchunks), dim3(kThreads), st, a);
+    launch(prof, kKScanHeader, k_scan_header, dim3(1), dim3(kScanThreads), st, a);
+    launch(prof, kKEncode, k_encode, dim3(nchunks), dim3(kThreads), st, a);
+    launch(prof, kKOutliers, k_outliers, dim3(nchunks), dim3(kThreads), st, a);
 }
 
 }  // namespace cmpz

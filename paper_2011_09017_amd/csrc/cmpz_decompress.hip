@@ -301,25 +301,27 @@ __global__ __launch_bounds__(kThreads) void k_col_scan_dequant(DecompressArgs a)
 
 size_t decode_tables_bytes() { return sizeof(DecodeTables); }
 
-void launch_decompress_with_tables(const DecompressArgs &a, void *tables, hipStream_t st)
+void launch_decompress(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st)
 {
     DecodeTables *tb = static_cast<DecodeTables *>(tables);
-    hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(1024), 0, st, a, tb);
+    launch(prof, kKDecodeTables, k_decode_tables, dim3(1), dim3(1024), st, a, tb);
     if (a.numel == 0) return;
+    const DecodeTables *ctb = tb;
     const uint64_t nsubs = (uint64_t)a.lay.nchunks * a.lay.nsub;
     const uint32_t blocks = (uint32_t)((nsubs + kDecThreads - 1) / kDecThreads);
     switch (a.sub) {
-    case 32:  hipLaunchKernelGGL(k_decode<32>, dim3(blocks), dim3(kDecThreads), 0, st, a, tb); break;
-    case 64:  hipLaunchKernelGGL(k_decode<64>, dim3(blocks), dim3(kDecThreads), 0, st, a, tb); break;
-    default:  hipLaunchKernelGGL(k_decode<128>, dim3(blocks), dim3(kDecThreads), 0, st, a, tb); break;
+    case 32:  launch(prof, kKDecode, k_decode<32>, dim3(blocks), dim3(kDecThreads), st, a, ctb); break;
+    case 64:  launch(prof, kKDecode, k_decode<64>, dim3(blocks), dim3(kDecThreads), st, a, ctb); break;
+    default:  launch(prof, kKDecode, k_decode<128>, dim3(blocks), dim3(kDecThreads), st, a, ctb); break;
     }
-    hipLaunchKernelGGL(k_patch_outliers, dim3(256), dim3(kThreads), 0, st, a, tb);
+    launch(prof, kKPatchOutliers, k_patch_outliers, dim3(256), dim3(kThreads), st, a, ctb);
+    const uint64_t cap = 65536ull * 8;
     const uint64_t rows = (uint64_t)a.planes * a.H;
-    const uint32_t rblocks = (uint32_t)((rows + 3) / 4 < 65536 * 8 ? (rows + 3) / 4 : 65536 * 8);
-    hipLaunchKernelGGL(k_row_scan, dim3(rblocks), dim3(kThreads), 0, st, a);
+    const uint64_t rblocks = (rows + 3) / 4 < cap ? (rows + 3) / 4 : cap;
+    launch(prof, kKRowScan, k_row_scan, dim3((uint32_t)rblocks), dim3(kThreads), st, a);
     const uint64_t cols = (uint64_t)a.planes * a.W;
-    const uint32_t cblocks = (uint32_t)((cols + kThreads - 1) / kThreads < 65536 * 8 ? (cols + kThreads - 1) / kThreads : 65536 * 8);
-    hipLaunchKernelGGL(k_col_scan_dequant, dim3(cblocks), dim3(kThreads), 0, st, a);
+    const uint64_t cblocks = (cols + kThreads - 1) / kThreads < cap ? (cols + kThreads - 1) / kThreads : cap;
+    launch(prof, kKColScanDequant, k_col_scan_dequant, dim3((uint32_t)cblocks), dim3(kThreads), st, a);
 }
 
 }  // namespace cmpz

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 namespace cmpz {
 
 constexpr int      kWave        = 64;       // CDNA wavefront
@@ -90,7 +92,44 @@ struct DecompressArgs {
     uint32_t *status;
 };
 
-void launch_compress(const CompressArgs &a, hipStream_t st);
-void launch_decompress(const DecompressArgs &a, hipStream_t st);
+// Kernel identifiers for the optional per-kernel timing (cmp_profile).
+enum KernelId : int {
+    kKQuantLorenzoHist = 0, kKCodebook, kKChunkBits, kKScanHeader, kKEncode, kKOutliers, kKEmpty,
+    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKernelCount
+};
+extern const char *const kKernelNames[kKernelCount];
+
+// When enabled, every launch is bracketed by two events on its stream.
+struct Profiler {
+    struct Rec { int id; hipEvent_t beg, end; };
+    bool enabled = false;
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    size_t used = 0;
+    hipEvent_t get()
+    {
+        if (used == pool.size()) { hipEvent_t e; (void)hipEventCreate(&e); pool.push_back(e); }
+        return pool[used++];
+    }
+};
+
+template <class K, class... A>
+inline void launch(Profiler *p, int id, K kernel, dim3 grid, dim3 block, hipStream_t st, A... args)
+{
+    if (p && p->enabled) {
+        Profiler::Rec r{id, p->get(), p->get()};
+        (void)hipEventRecord(r.beg, st);
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+        (void)hipEventRecord(r.end, st);
+        p->recs.push_back(r);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+    }
+}
+
+void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st);
+void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st);
+size_t decode_tables_bytes();
+void launch_decompress(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st);
 
 }  // namespace cmpz
