@@ -118,6 +118,7 @@ int cmp_last_status(cmp_ctx *ctx, void *stream);
 #define CMP_STAGE_HIST        1   /* uint32[2*radius]: occurrences of each symbol              */
 #define CMP_STAGE_LENS        2   /* uint8[2*radius]: Huffman code length, 0 = unused          */
 #define CMP_STAGE_CODES       3   /* uint64[2*radius]: length << 56 | canonical code           */
+#define CMP_STAGE_COUNTERS    4   /* uint32[64]: the context's control words (diagnostics only) */
 int cmp_debug_stage(cmp_ctx *ctx, int which, const void **d_ptr, size_t *bytes);
 
 /* Per-kernel timing for benchmarks.  cmp_profile(ctx, 1) clears the record and makes

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcmpz.so")
 
 CMP_OK, CMP_E_ARG, CMP_E_NOSPACE, CMP_E_FORMAT, CMP_E_MISMATCH, CMP_E_HIP, CMP_W_RANGE = 0, -1, -2, -3, -4, -5, 1
-CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES = 0, 1, 2, 3
+CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES, CMP_STAGE_COUNTERS = 0, 1, 2, 3, 4
 
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
            "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",

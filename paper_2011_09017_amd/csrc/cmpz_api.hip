@@ -12,7 +12,7 @@ namespace cmpz {
 const char *const kKernelNames[kKernelCount] = {
     "k_quant_lorenzo_split_hist", "k_codebook", "k_chunk_bits", "k_scan_header", "k_encode", "k_outliers",
     "k_empty_container", "k_decode_tables", "k_decode", "k_patch_outliers", "k_row_scan",
-    "k_col_scan_dequant"};
+    "k_col_scan_dequant", "k_decode_fused"};
 }  // namespace cmpz
 
 using namespace cmpz;
@@ -306,6 +306,7 @@ int cmp_debug_stage(cmp_ctx *ctx, int which, const void **d_ptr, size_t *bytes)
     case CMP_STAGE_HIST: *d_ptr = ctx->d_hist_copy; *bytes = 4 * nsym; return CMP_OK;
     case CMP_STAGE_LENS: *d_ptr = ctx->d_lens; *bytes = nsym; return CMP_OK;
     case CMP_STAGE_CODES: *d_ptr = ctx->d_codes; *bytes = 8 * nsym; return CMP_OK;
+    case CMP_STAGE_COUNTERS: *d_ptr = ctx->d_meta; *bytes = 4 * kMetaWords; return CMP_OK;
     default: return CMP_E_ARG;
     }
 }

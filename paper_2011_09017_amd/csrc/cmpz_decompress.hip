@@ -5,29 +5,13 @@
 // This first path stages the residuals as int32 in the output buffer itself and
 // turns them into fp32 in place: decode -> patch -> row scan -> column scan with
 // de-quantisation.  It needs no scratch and works for any H and W.
-#include "cmpz_internal.h"
+#include "cmpz_decode_core.h"
 
 namespace cmpz {
 namespace {
 
 constexpr int      kThreads  = 256;
 constexpr int      kDecThreads = 128;              // sub-blocks (lanes) per decode workgroup
-constexpr uint32_t kLB       = 10;                 // bits resolved by the direct lookup table
-constexpr uint32_t kFastSize = 1u << kLB;
-
-// Decode tables kept in context scratch between the table kernel and the decoders.
-struct DecodeTables {
-    uint32_t fast[kFastSize];     // symbol | length << 16, length 0 = longer than kLB bits
-    uint64_t first[64];           // first canonical code of each length
-    uint32_t count[64];           // codes of each length
-    uint32_t offs[64];            // index into sorted[] of the first symbol of each length
-    uint16_t sorted[kMaxSym];     // symbols ordered by (length, symbol)
-    uint32_t max_len;
-    uint32_t payload_units;
-    uint32_t n_outliers;
-    uint32_t pad;
-};
-
 __device__ __forceinline__ uint64_t align16(uint64_t v) { return (v + 15) & ~15ull; }
 
 // ---------------------------------------------------------------------------
@@ -37,7 +21,8 @@ __device__ __forceinline__ uint64_t align16(uint64_t v) { return (v + 15) & ~15u
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, DecodeTables *tb)
 {
-    __shared__ uint32_t len_of[kMaxSym];
+    __shared__ DecodeTables T;
+    __shared__ uint32_t wave_cnt[16][64];
     __shared__ uint32_t bl_count[64];
     __shared__ uint64_t first_code[64];
     __shared__ uint32_t offs[64];
@@ -76,8 +61,8 @@ __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, Decode
                 const uint32_t *outl_off = reinterpret_cast<const uint32_t *>(a.buf + l.off_outl_off);
                 if (chunk_off[0] != 0 || chunk_off[l.nchunks] != units) bad = kStFormat;
                 if (outl_off[0] != 0 || outl_off[l.nchunks] != (uint32_t)n_out) bad = kStFormat;
-                tb->payload_units = units;
-                tb->n_outliers = (uint32_t)n_out;
+                T.payload_units = units;
+                T.n_outliers = (uint32_t)n_out;
             }
         }
         bad_s = bad; used_s = 0; max_len_s = 0; kraft_s = 0;
@@ -94,7 +79,6 @@ __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, Decode
     if ((uint32_t)tid < nsym) L = a.buf[a.lay.off_lens + tid];
     else if ((uint32_t)tid < ((nsym + 15u) & ~15u)) { if (a.buf[a.lay.off_lens + tid]) atomicOr(&bad_s, kStFormat); }
     if (L > kMaxCodeLen) { atomicOr(&bad_s, kStFormat); L = 0; }
-    len_of[tid] = L;
     if (L) {
         atomicAdd(&used_s, 1u);
         atomicAdd(&kraft_s, 1ull << (56 - L));
@@ -116,6 +100,13 @@ __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, Decode
             offs[k] = o;
             o += bl_count[k];
         }
+        // left-aligned end of the codes of at most kLB bits, and the level-2 geometry
+        const uint64_t t = (first_code[kLB] + bl_count[kLB]) << (32 - kLB);
+        const uint64_t span = (1ull << 32) - t;              // code space of the longer codes
+        uint32_t sh = 0;
+        while ((span >> sh) > kT2Size) ++sh;
+        T.t32 = (uint32_t)t; T.sh = sh; T.has_long = (max_len_s > kLB && span > 0) ? 1u : 0u;
+        T.max_len = max_len_s;
     }
     __syncthreads();
     if (bad_s) {
@@ -123,50 +114,67 @@ __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, Decode
         return;
     }
 
-    __shared__ uint32_t fast_s[kFastSize];
-    for (uint32_t k = tid; k < kFastSize; k += 1024) fast_s[k] = 0;
+    // symbols ordered by (length, symbol)
+    const uint32_t rank = rank_within_length(L, wave_cnt, tid);
+    if (L) T.sorted[offs[L] + rank] = (uint16_t)tid;
+    if (tid < 64) { T.first[tid] = first_code[tid]; T.count[tid] = bl_count[tid]; T.offs[tid] = offs[tid]; }
     __syncthreads();
-    if (L) {
-        uint32_t rank = 0;
-        for (int j = 0; j < tid; ++j) rank += (len_of[j] == L) ? 1u : 0u;
-        const uint64_t code = first_code[L] + rank;
-        tb->sorted[offs[L] + rank] = (uint16_t)tid;
-        if (L <= kLB) {
-            const uint32_t lo = (uint32_t)code << (kLB - L), n = 1u << (kLB - L);
-            const uint32_t e = (uint32_t)tid | (L << 16);
-            for (uint32_t k = 0; k < n; ++k) fast_s[lo + k] = e;
+
+    // level 1: entry idx is the codeword (if any, of at most kLB bits) that prefixes idx
+    for (uint32_t idx = tid; idx < kT1Size; idx += 1024) {
+        uint32_t e = 0;
+        for (uint32_t l = 1; l <= kLB; ++l) {
+            const uint32_t code = idx >> (kLB - l);
+            const uint32_t f = (uint32_t)first_code[l];
+            if (code >= f && code - f < bl_count[l]) { e = T.sorted[offs[l] + code - f] | (l << 10); break; }
         }
+        T.t1[idx] = (uint16_t)e;
+    }
+    // level 2: entry i covers left-aligned values t32 + [i << sh, (i+1) << sh)
+    {
+        const uint32_t idx = tid;                            // kT2Size == 1024 threads
+        uint32_t e = 0;
+        const uint64_t v = (uint64_t)T.t32 + ((uint64_t)idx << T.sh);
+        if (T.has_long && v < (1ull << 32)) {
+            const uint32_t lmax = (32 - T.sh < T.max_len) ? 32 - T.sh : T.max_len;
+            for (uint32_t l = kLB + 1; l <= lmax; ++l) {
+                const uint64_t code = v >> (32 - l);
+                if (code >= first_code[l] && code - first_code[l] < bl_count[l]) {
+                    e = T.sorted[offs[l] + (uint32_t)(code - first_code[l])] | (l << 10);
+                    break;
+                }
+            }
+        }
+        T.t2[idx] = (uint16_t)e;
     }
     __syncthreads();
-    for (uint32_t k = tid; k < kFastSize; k += 1024) tb->fast[k] = fast_s[k];
-    if (tid < 64) { tb->first[tid] = first_code[tid]; tb->count[tid] = bl_count[tid]; tb->offs[tid] = offs[tid]; }
-    if (tid == 0) { tb->max_len = max_len_s; a.meta[kMetaBad] = 0; }
+    {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(&T);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(tb);
+        for (uint32_t k = tid; k < sizeof(DecodeTables) / 4; k += 1024) dst[k] = src[k];
+    }
+    if (tid == 0) a.meta[kMetaBad] = 0;
 }
 
 // ---------------------------------------------------------------------------
-// Chunked Huffman decode: one lane per sub-block, 128 sub-blocks per workgroup.
-// Symbols go to an LDS stage (odd word stride per lane, conflict free) and leave
-// as int32 residuals with coalesced stores.  Outliers (symbol 0) are patched by
-// the next kernel.
+// Unfused path, for shapes the fused kernel does not take.  Chunked Huffman
+// decode: one lane per sub-block, 128 sub-blocks per workgroup.  Symbols go to an
+// LDS stage (odd word stride per lane, conflict free) and leave as int32
+// residuals with coalesced stores.  Outliers (symbol 0) are patched by the next
+// kernel.
 // ---------------------------------------------------------------------------
 template <int SUB>
 __global__ __launch_bounds__(kDecThreads) void k_decode(DecompressArgs a, const DecodeTables *__restrict__ tb)
 {
     constexpr int kStride = SUB + 2;                       // u16 units; (SUB+2)/2 words is odd
-    __shared__ uint32_t fast[kFastSize];
-    __shared__ uint64_t first[64];
-    __shared__ uint32_t count[64], offs[64];
-    __shared__ uint16_t sorted[kMaxSym];
+    __shared__ DecodeTables T;
     __shared__ uint16_t stage[kDecThreads * kStride];
     if (a.meta[kMetaBad]) return;
     const int tid = threadIdx.x;
-    for (int k = tid; k < (int)kFastSize; k += kDecThreads) fast[k] = tb->fast[k];
-    for (int k = tid; k < (int)kMaxSym; k += kDecThreads) sorted[k] = tb->sorted[k];
-    if (tid < 64) { first[tid] = tb->first[tid]; count[tid] = tb->count[tid]; offs[tid] = tb->offs[tid]; }
+    load_tables(T, tb, tid, kDecThreads);
     __syncthreads();
 
     constexpr uint32_t nsub = kChunk / SUB;
-    const uint32_t max_len = tb->max_len;
     const uint32_t R = a.radius;
     const uint64_t g = (uint64_t)blockIdx.x * kDecThreads + tid;      // global sub-block index
     const uint32_t c = (uint32_t)(g / nsub), j = (uint32_t)(g % nsub);
@@ -180,50 +188,21 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecompressArgs a, const 
         const uint16_t *sub_bits = reinterpret_cast<const uint16_t *>(a.buf + a.lay.off_sub_bits) + (uint64_t)c * nsub;
         const uint32_t u0 = chunk_off[c], u1 = chunk_off[c + 1];
         uint32_t nwords = 0;
-        if (u0 <= u1 && u1 <= tb->payload_units) nwords = (u1 - u0) * 4; else bad = true;
+        if (u0 <= u1 && u1 <= T.payload_units) nwords = (u1 - u0) * 4; else bad = true;
         const uint32_t *__restrict__ words =
             reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_payload + (uint64_t)(bad ? 0u : u0) * 16);
         uint32_t start = 0;
         for (uint32_t k = 0; k < j; ++k) start += sub_bits[k];
         const uint32_t sb = sub_bits[j];
-        if ((uint64_t)start + sb > (uint64_t)nwords * 32) bad = true;
-
-        auto rd = [&](uint32_t k) -> uint32_t { return k < nwords ? words[k] : 0u; };
-        uint32_t pos = start;
-        uint32_t wi = pos >> 5;
-        uint64_t win = ((((uint64_t)rd(wi)) << 32) | rd(wi + 1)) << (pos & 31);
-        int avail = 64 - (int)(pos & 31);
-        wi += 2;
+        if ((uint64_t)start + sb > (uint64_t)nwords * 32) { bad = true; nwords = 0; }
         uint16_t *my = stage + tid * kStride;
-        for (uint32_t k = 0; k < n_here; ++k) {
-            if (avail <= 32) { win |= ((uint64_t)rd(wi++)) << (32 - avail); avail += 32; }
-            const uint32_t e = fast[(uint32_t)(win >> (64 - kLB))];
-            uint32_t len = e >> 16, s = e & 0xffffu;
-            if (len == 0) {
-                // codeword longer than the table: canonical search on a fresh 64-bit window
-                const uint32_t w0 = pos >> 5, off = pos & 31;
-                uint64_t w64 = ((((uint64_t)rd(w0)) << 32) | rd(w0 + 1)) << off;
-                if (off) w64 |= (uint64_t)(rd(w0 + 2) >> (32 - off));
-                for (uint32_t L = kLB + 1; L <= max_len; ++L) {
-                    const uint64_t code = w64 >> (64 - L);
-                    if (code >= first[L] && code - first[L] < count[L]) {
-                        s = sorted[offs[L] + (uint32_t)(code - first[L])];
-                        len = L;
-                        break;
-                    }
-                }
-                if (len == 0) { bad = true; len = 1; s = R; }
-                pos += len;
-                wi = pos >> 5;
-                win = ((((uint64_t)rd(wi)) << 32) | rd(wi + 1)) << (pos & 31);
-                avail = 64 - (int)(pos & 31);
-                wi += 2;
-            } else {
-                win <<= len; avail -= (int)len; pos += len;
-            }
-            my[k] = (uint16_t)s;
+        uint32_t end = 0;
+        if (nwords) {
+            const uint32_t last = nwords - 1;
+            end = decode_run(T, [&](uint32_t k) -> uint32_t { return words[k < last ? k : last]; }, start, n_here, 0u, R,
+                             [&](uint32_t k, uint32_t sy) { my[k] = (uint16_t)sy; }, bad);
         }
-        if (pos != start + sb) bad = true;
+        if (end != start + sb) bad = true;
     }
     if (bad) atomicOr(a.status, kStFormat);
     __syncthreads();
@@ -307,6 +286,8 @@ void launch_decompress(const DecompressArgs &a, void *tables, Profiler *prof, hi
     launch(prof, kKDecodeTables, k_decode_tables, dim3(1), dim3(1024), st, a, tb);
     if (a.numel == 0) return;
     const DecodeTables *ctb = tb;
+    if (launch_decode_fused(a, ctb, prof, st)) return;
+    // shapes the fused kernel does not take: residuals staged in the output buffer
     const uint64_t nsubs = (uint64_t)a.lay.nchunks * a.lay.nsub;
     const uint32_t blocks = (uint32_t)((nsubs + kDecThreads - 1) / kDecThreads);
     switch (a.sub) {

@@ -55,7 +55,8 @@ enum MetaWord : int {
     kMetaSkip        = 2,   // nonzero: container does not fit, later kernels write nothing
     kMetaNOutliers   = 3,
     kMetaBad         = 4,   // decompress: nonzero when the container failed validation
-    kMetaWords       = 16
+    kMetaClocks      = 16,  // 24 uint64 phase-clock accumulators (only in CMPZ_PHASE_CLOCKS builds)
+    kMetaWords       = 64
 };
 
 struct CompressArgs {
@@ -92,10 +93,97 @@ struct DecompressArgs {
     uint32_t *status;
 };
 
+constexpr uint32_t kLB = 11;                      // bits resolved by the first decode table
+struct DecodeTables;                              // cmpz_decode_core.h
+
+// Exact n / d for 32-bit n and d via one 64x32 high multiply (M = ceil(2^64 / d)).
+struct FastDiv {
+    uint32_t d, mhi, mlo;
+    __host__ static FastDiv make(uint32_t d)
+    {
+        FastDiv f;
+        f.d = d ? d : 1;
+        const uint64_t m = f.d > 1 ? (~0ull / f.d) + 1 : 0;
+        f.mhi = (uint32_t)(m >> 32);
+        f.mlo = (uint32_t)m;
+        return f;
+    }
+    __device__ __forceinline__ uint32_t div(uint32_t n) const
+    {
+        if (d == 1) return n;
+        const uint64_t t = (uint64_t)mhi * n + __umulhi(mlo, n);
+        return (uint32_t)(t >> 32);
+    }
+};
+
+// --- wave-level scans on the DPP network (row shifts inside 16-lane rows, then the two
+// row broadcasts that CDNA keeps from GCN); no LDS traffic, unlike __shfl_up ---------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t src)
+{
+    // lanes without a valid source lane, and rows outside ROW_MASK, read 0
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)src, CTRL, ROW_MASK, 0xf, false);
+}
+
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x)
+{
+    x += dpp_u32<0x111, 0xf>(x);     // row_shr:1
+    x += dpp_u32<0x112, 0xf>(x);     // row_shr:2
+    x += dpp_u32<0x114, 0xf>(x);     // row_shr:4
+    x += dpp_u32<0x118, 0xf>(x);     // row_shr:8
+    x += dpp_u32<0x142, 0xa>(x);     // row_bcast:15 into rows 1 and 3
+    x += dpp_u32<0x143, 0xc>(x);     // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+// inclusive segmented prefix sum: f != 0 marks the first lane of a segment; on return f is
+// nonzero for every lane at or after the first segment start of the wave
+#define CMPZ_SEG_STEP(CTRL, MASK)                                   \
+    {                                                               \
+        const uint32_t pv = dpp_u32<CTRL, MASK>((uint32_t)v);       \
+        const uint32_t pf = dpp_u32<CTRL, MASK>(f);                 \
+        v = f ? v : v + (int32_t)pv;                                \
+        f |= pf;                                                    \
+    }
+__device__ __forceinline__ void wave_segmented_sum(int32_t &v, uint32_t &f)
+{
+    CMPZ_SEG_STEP(0x111, 0xf)
+    CMPZ_SEG_STEP(0x112, 0xf)
+    CMPZ_SEG_STEP(0x114, 0xf)
+    CMPZ_SEG_STEP(0x118, 0xf)
+    CMPZ_SEG_STEP(0x142, 0xa)
+    CMPZ_SEG_STEP(0x143, 0xc)
+}
+#undef CMPZ_SEG_STEP
+
+// For each of 1024 symbols (one per thread, 16 waves): how many symbols with a smaller index
+// have the same nonzero code length L.  wave_cnt is LDS scratch; contains a barrier.
+__device__ __forceinline__ uint32_t rank_within_length(uint32_t L, uint32_t (*wave_cnt)[64], int tid)
+{
+    const int lane = tid & 63, wv = tid >> 6;
+    for (int k = tid; k < 16 * 64; k += 1024) (&wave_cnt[0][0])[k] = 0;
+    __syncthreads();
+    uint32_t in_wave = 0;
+    unsigned long long remaining = __ballot(L != 0);
+    while (remaining) {                                   // wave-uniform
+        const int leader = __ffsll((long long)remaining) - 1;
+        const uint32_t Lx = __shfl(L, leader);
+        const unsigned long long m = __ballot(L == Lx);
+        if (L == Lx) in_wave = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+        if (lane == leader) wave_cnt[wv][Lx & 63u] = (uint32_t)__popcll(m);
+        remaining &= ~m;
+    }
+    __syncthreads();
+    uint32_t base = 0;
+    if (L) for (int k = 0; k < wv; ++k) base += wave_cnt[k][L & 63u];
+    return base + in_wave;
+}
+
 // Kernel identifiers for the optional per-kernel timing (cmp_profile).
 enum KernelId : int {
     kKQuantLorenzoHist = 0, kKCodebook, kKChunkBits, kKScanHeader, kKEncode, kKOutliers, kKEmpty,
-    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKernelCount
+    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKernelCount
 };
 extern const char *const kKernelNames[kKernelCount];
 
@@ -131,5 +219,6 @@ void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st);
 void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st);
 size_t decode_tables_bytes();
 void launch_decompress(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st);
+bool launch_decode_fused(const DecompressArgs &a, const DecodeTables *tb, Profiler *prof, hipStream_t st);
 
 }  // namespace cmpz

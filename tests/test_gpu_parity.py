@@ -104,6 +104,17 @@ def test_sub_and_radius_variants(gpu, orc, sub, radius):
         assert h["n_outliers"] > 0
 
 
+@pytest.mark.parametrize("sub", [32, 64, 128])
+@pytest.mark.parametrize("shape", [(1, 3, 224, 224), (2, 2, 112, 112), (1, 1, 500, 256), (1, 1, 40, 257),
+                                   (1, 1, 300, 300), (3, 300, 7, 7), (1, 2, 129, 63)])
+def test_band_and_group_shapes(gpu, orc, sub, shape):
+    """Planes larger than one band, groups of small planes, and shapes that take the unfused kernels."""
+    ctx = make_ctx(gpu, sub=sub)
+    x = activation(shape, 5, 0.5, seed=sub + shape[3]).numpy()
+    x[0, 0, shape[2] // 2, shape[3] // 3] = 300.0           # one outlier cluster
+    check_case(gpu, orc, x, 1e-2, ctx, orc.Config(sub=sub))
+
+
 def test_all_zero_constant_and_single_symbol(gpu, orc):
     ctx = make_ctx(gpu)
     x = np.zeros((2, 2, 30, 30), np.float32)
