@@ -23,7 +23,8 @@ struct cmp_ctx {
     uint64_t   max_chunks;
     uint8_t   *d_base;          // one allocation, carved up below
     uint16_t  *d_sym;
-    uint32_t  *d_hist, *d_hist_copy, *d_chunk_units, *d_outl_cnt, *d_meta, *d_status;
+    uint32_t  *d_hist, *d_hist_copy, *d_meta, *d_status, *d_outl_cnt;
+    uint64_t  *d_desc;
     uint8_t   *d_lens;
     uint64_t  *d_codes;
     void      *d_tables;
@@ -98,6 +99,7 @@ struct DeviceGuard {
 
 int status_to_code(uint32_t st)
 {
+    if (st & kStInternal) return CMP_E_HIP;
     if (st & kStFormat) return CMP_E_FORMAT;
     if (st & kStMismatch) return CMP_E_MISMATCH;
     if (st & kStNoSpace) return CMP_E_NOSPACE;
@@ -141,7 +143,7 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     const uint64_t o_sym = carve(2 * (c.max_numel + 16));
     const uint64_t o_hist = carve(4 * kMaxSym);
     const uint64_t o_hist_copy = carve(4 * kMaxSym);
-    const uint64_t o_units = carve(4 * (ctx->max_chunks + 1));
+    const uint64_t o_desc = carve(8 * (ctx->max_chunks + 1));
     const uint64_t o_ocnt = carve(4 * (ctx->max_chunks + 1));
     const uint64_t o_meta = carve(4 * kMetaWords);
     const uint64_t o_status = carve(4);
@@ -156,7 +158,7 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     ctx->d_sym = reinterpret_cast<uint16_t *>(ctx->d_base + o_sym);
     ctx->d_hist = reinterpret_cast<uint32_t *>(ctx->d_base + o_hist);
     ctx->d_hist_copy = reinterpret_cast<uint32_t *>(ctx->d_base + o_hist_copy);
-    ctx->d_chunk_units = reinterpret_cast<uint32_t *>(ctx->d_base + o_units);
+    ctx->d_desc = reinterpret_cast<uint64_t *>(ctx->d_base + o_desc);
     ctx->d_outl_cnt = reinterpret_cast<uint32_t *>(ctx->d_base + o_ocnt);
     ctx->d_meta = reinterpret_cast<uint32_t *>(ctx->d_base + o_meta);
     ctx->d_status = reinterpret_cast<uint32_t *>(ctx->d_base + o_status);
@@ -218,7 +220,10 @@ int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float e
     a.r = r;
     a.sym = ctx->d_sym; a.hist = ctx->d_hist; a.hist_copy = ctx->d_hist_copy;
     a.lens = ctx->d_lens; a.codes = ctx->d_codes;
-    a.chunk_units = ctx->d_chunk_units; a.outl_cnt = ctx->d_outl_cnt;
+    a.desc = ctx->d_desc; a.outl_cnt = ctx->d_outl_cnt;
+    // encode tiles: as large as still leaves a few thousand of them to spread over the chip
+    a.tile_chunks = 8;
+    while (a.tile_chunks > 1 && (a.lay.nchunks + a.tile_chunks - 1) / a.tile_chunks < 2048) a.tile_chunks >>= 1;
     a.meta = ctx->d_meta; a.status = ctx->d_status;
 
     DeviceGuard guard(ctx->device);

@@ -5,75 +5,132 @@
 // (count, symbol); two FIFO queues, leaves and internal nodes in creation order;
 // the lighter head is taken, a leaf before an internal node of equal weight.
 // Codes are canonical: ordered by (length, symbol), first code 0, read MSB first.
+//
+// Only the merge itself is serial (one lane, n-1 steps for n used symbols); it
+// keeps the heads of both queues in registers and fetches their successors one
+// step ahead, so a step costs ALU time only.  Sorting is by counting ranks,
+// depths by walking parent links, ranks within a length by wave ballots.
 #include "cmpz_internal.h"
 
 namespace cmpz {
 namespace {
 
 constexpr int kCbThreads = 1024;
+constexpr uint32_t kInf = 0xffffffffu;       // "queue empty"; a real weight reaches it only at the root
+
+#ifdef CMPZ_PHASE_CLOCKS
+#define PHASE(k) if (tid == 0) { const long long now_ = clock64(); clk[k] += now_ - last_; last_ = now_; }
+#else
+#define PHASE(k)
+#endif
 
 __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
 {
-    __shared__ uint64_t key[kMaxSym];            // count << 10 | symbol, unused = all ones
-    __shared__ uint64_t weight[2 * kMaxSym];     // node weights: leaves 0..n-1, internal n..2n-2
-    __shared__ uint16_t parent[2 * kMaxSym];
+#ifdef CMPZ_PHASE_CLOCKS
+    long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    long long last_ = clock64();
+#endif
+    __shared__ uint64_t key[kMaxSym];            // used symbols, compacted: count << 10 | symbol
+    __shared__ uint32_t leaf_w[kMaxSym + 192];   // leaf weights, ascending, padded with kInf
+    __shared__ uint16_t leaf_sym[kMaxSym];
+    __shared__ uint32_t node_w[kMaxSym + 192];   // internal node weights in creation order, kInf = not made
+    __shared__ uint16_t parent[2 * kMaxSym];     // node ids: leaves 0..n-1, internal n..2n-2
+    __shared__ uint32_t merge_log[kMaxSym + 64]; // children of each internal node, two 16-bit ids
     __shared__ uint32_t len_of[kMaxSym];         // code length per symbol
+    __shared__ uint32_t wave_cnt[16][64];
     __shared__ uint32_t bl_count[64];
     __shared__ uint64_t first_code[64];
-    __shared__ uint32_t n_used_s, max_len_s;
+    __shared__ uint32_t wave_used[16];
+    __shared__ uint32_t max_len_s;
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const uint32_t nsym = 2 * a.radius;
 
     // 1. fetch the histogram, leave it zeroed for the next call, keep a copy for inspection
     uint32_t cnt = 0;
-    if ((uint32_t)tid < nsym) { cnt = a.hist[tid]; }
+    if ((uint32_t)tid < nsym) cnt = a.hist[tid];
     a.hist[tid] = 0;
     a.hist_copy[tid] = cnt;
-    key[tid] = cnt ? (((uint64_t)cnt << 10) | (uint64_t)tid) : ~0ull;
     len_of[tid] = 0;
     if (tid < 64) { bl_count[tid] = 0; first_code[tid] = 0; }
-    if (tid == 0) { n_used_s = 0; max_len_s = 0; }
-    __syncthreads();
-    if (cnt) atomicAdd(&n_used_s, 1u);
+    if (tid == 0) max_len_s = 0;
 
-    // 2. bitonic sort of the 1024 keys, ascending
-    for (uint32_t k = 2; k <= kMaxSym; k <<= 1) {
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            __syncthreads();
-            const uint32_t ixj = (uint32_t)tid ^ j;
-            if (ixj > (uint32_t)tid) {
-                const uint64_t x = key[tid], y = key[ixj];
-                const bool up = ((uint32_t)tid & k) == 0;
-                if ((x > y) == up) { key[tid] = y; key[ixj] = x; }
+    PHASE(0)
+    // 2. compact the used symbols (ballot + per-wave offsets)
+    const unsigned long long used_mask = __ballot(cnt != 0);
+    if (lane == 0) wave_used[wv] = (uint32_t)__popcll(used_mask);
+    __syncthreads();
+    uint32_t n = 0, my_slot = 0;
+    for (int k = 0; k < 16; ++k) { if (k < wv) my_slot += wave_used[k]; n += wave_used[k]; }
+    my_slot += (uint32_t)__popcll(used_mask & ((1ull << lane) - 1ull));
+    if (cnt) key[my_slot] = ((uint64_t)cnt << 10) | (uint64_t)tid;
+    __syncthreads();
+
+    PHASE(1)
+    // 3. sort by counting: the rank of a key is the number of smaller keys (keys are distinct)
+    if ((uint32_t)tid < n) {
+        const uint64_t mine = key[tid];
+        uint32_t rank = 0;
+#pragma unroll 8
+        for (uint32_t j = 0; j < n; ++j) rank += (key[j] < mine) ? 1u : 0u;
+        leaf_w[rank] = (uint32_t)(mine >> 10);
+        leaf_sym[rank] = (uint16_t)(mine & 1023u);
+    }
+    if ((uint32_t)tid < 192) leaf_w[n + tid] = kInf;
+    node_w[tid] = kInf;
+    if (tid < 192) node_w[kMaxSym + tid] = kInf;
+    __syncthreads();
+
+    PHASE(2)
+    // 4. two-queue merge by wave 0 with uniform (scalar) control flow and no LDS traffic in
+    //    the common step.  Lane j of LB holds the weight of leaf lbase+j, lane j of IB that of
+    //    internal node ibase+j (kInf = not made yet); the queue heads are read with v_readlane.
+    //    Step m makes internal node m; its weight and its two children are logged in lane m%64
+    //    of WLOG / PLOG, which are written to LDS once per 64 steps.
+    if (wv == 0 && n >= 2) {
+        uint32_t LB = leaf_w[lane], IB = kInf, WLOG = kInf, PLOG = 0;
+        uint32_t lbase = 0, ibase = 0, ql = 0, qi = 0;
+        const uint32_t steps = n - 1;
+        for (uint32_t m = 0; m < steps; ++m) {
+            // rare: slide a window, or start a new log block
+            if (ql + 1 - lbase >= 64) { lbase = ql; LB = leaf_w[ql + lane]; }
+            if ((m & 63u) == 0 && m != 0) {
+                node_w[m - 64 + lane] = WLOG; merge_log[m - 64 + lane] = PLOG;
+                WLOG = kInf;
             }
+            if (qi + 1 - ibase >= 64) {
+                // every node made so far must be readable from LDS: flush the open log block too
+                node_w[(m & ~63u) + lane] = WLOG;
+                ibase = qi;
+                IB = node_w[qi + lane];                     // entries at or past m are still kInf
+            }
+            const uint32_t l0 = (uint32_t)__builtin_amdgcn_readlane((int)LB, (int)(ql - lbase));
+            const uint32_t l1 = (uint32_t)__builtin_amdgcn_readlane((int)LB, (int)(ql + 1 - lbase));
+            const uint32_t i0 = (uint32_t)__builtin_amdgcn_readlane((int)IB, (int)(qi - ibase));
+            const uint32_t i1 = (uint32_t)__builtin_amdgcn_readlane((int)IB, (int)(qi + 1 - ibase));
+            uint32_t wsum, kids;                             // children ids, low and high half
+            if (l1 <= i0) { wsum = l0 + l1; kids = ql | ((ql + 1) << 16); ql += 2; }              // two leaves (a leaf wins ties)
+            else if (i1 < l0) { wsum = i0 + i1; kids = (n + qi) | ((n + qi + 1) << 16); qi += 2; } // two internal nodes
+            else { wsum = l0 + i0; kids = ql | ((n + qi) << 16); ql += 1; qi += 1; }              // one of each
+            const uint32_t slot = m & 63u;
+            WLOG = ((uint32_t)lane == slot) ? wsum : WLOG;
+            PLOG = ((uint32_t)lane == slot) ? kids : PLOG;
+            IB = ((uint32_t)lane == m - ibase) ? wsum : IB;  // m - ibase >= 64 selects no lane
         }
+        const uint32_t blk = (steps - 1) & ~63u;             // the open log block
+        node_w[blk + lane] = WLOG; merge_log[blk + lane] = PLOG;
     }
     __syncthreads();
-    const uint32_t n = n_used_s;
-
-    // 3. two-queue merge (serial, one lane)
-    if ((uint32_t)tid < n) weight[tid] = key[tid] >> 10;
-    __syncthreads();
-    if (tid == 0 && n >= 2) {
-        uint32_t q1 = 0, q2 = n, next = n;
-        while (next < 2 * n - 1) {
-            uint32_t pick[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const bool have_leaf = q1 < n, have_int = q2 < next;
-                if (have_leaf && (!have_int || weight[q1] <= weight[q2])) pick[t] = q1++;
-                else pick[t] = q2++;
-            }
-            weight[next] = weight[pick[0]] + weight[pick[1]];
-            parent[pick[0]] = (uint16_t)next;
-            parent[pick[1]] = (uint16_t)next;
-            ++next;
-        }
+    // parents from the log: step m made node n+m out of the two logged children
+    if ((uint32_t)tid + 1 < n) {
+        const uint32_t kids = merge_log[tid];
+        parent[kids & 0xffffu] = (uint16_t)(n + tid);
+        parent[kids >> 16] = (uint16_t)(n + tid);
     }
     __syncthreads();
 
-    // 4. depth of every leaf = its code length
+    PHASE(3)
+    // 5. depth of every leaf = its code length
     if ((uint32_t)tid < n) {
         uint32_t depth = 0;
         if (n == 1) depth = 1;
@@ -81,14 +138,14 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
             const uint32_t root = 2 * n - 2;
             for (uint32_t v = tid; v != root; v = parent[v]) ++depth;
         }
-        const uint32_t symbol = (uint32_t)(key[tid] & 1023u);
-        len_of[symbol] = depth;
+        len_of[leaf_sym[tid]] = depth;
         atomicAdd(&bl_count[depth & 63u], 1u);
         atomicMax(&max_len_s, depth);
     }
     __syncthreads();
 
-    // 5. canonical codes: first code of each length, then rank within the length
+    PHASE(4)
+    // 6. canonical codes: first code of each length, then rank within the length
     if (tid == 0) {
         uint64_t code = 0;
         for (int L = 1; L < 64; ++L) {
@@ -96,20 +153,21 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
             first_code[L] = code;
         }
     }
-    __syncthreads();
     const uint32_t L = len_of[tid];
-    uint64_t entry = 0;
-    if (L) {
-        uint32_t rank = 0;
-        for (int j = 0; j < tid; ++j) rank += (len_of[j] == L) ? 1u : 0u;
-        entry = ((uint64_t)L << 56) | (first_code[L] + rank);
-    }
+    const uint32_t rank = rank_within_length(L, wave_cnt, tid);       // contains barriers
+    const uint64_t entry = L ? (((uint64_t)L << 56) | (first_code[L] + rank)) : 0ull;
     a.codes[tid] = entry;
     a.lens[tid] = (uint8_t)L;
     // container section `lens`: 2*radius bytes, zero padded to a multiple of 16
     const uint32_t padded = (nsym + 15u) & ~15u;
     if ((uint32_t)tid < padded) a.out[a.lay.off_lens + tid] = ((uint32_t)tid < nsym) ? (uint8_t)L : 0;
     if (tid == 0) a.meta[kMetaMaxLen] = max_len_s;
+    PHASE(5)
+#ifdef CMPZ_PHASE_CLOCKS
+    if (tid == 0)
+        for (int k = 0; k < 8; ++k)
+            atomicAdd(reinterpret_cast<unsigned long long *>(a.meta + kMetaClocks) + 16 + k, (unsigned long long)clk[k]);
+#endif
 }
 
 }  // namespace

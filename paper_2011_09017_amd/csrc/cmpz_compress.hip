@@ -135,17 +135,17 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist(CompressA
     }
     if (tid < kTileChunks) {
         const uint64_t c = (uint64_t)blockIdx.x * kTileChunks + tid;
-        if (c < a.lay.nchunks) a.outl_cnt[c] = ocnt[tid];
+        if (c < a.lay.nchunks) {
+            a.outl_cnt[c] = ocnt[tid];
+            if (c % a.tile_chunks == 0) a.desc[c / a.tile_chunks] = 0;     // re-arm the encode sweep's scan
+        }
     }
     // range events: one atomic per wave
     for (int o = 32; o > 0; o >>= 1) events += __shfl_down(events, o);
     if ((tid & 63) == 0 && events) atomicAdd(&a.meta[kMetaRangeEvents], events);
 }
 
-// ---------------------------------------------------------------------------
-// Per-chunk bit counts: sub_bits (into the container) and the chunk's payload
-// size in 16-byte units (scratch).  One workgroup per chunk, 16 symbols a thread.
-// ---------------------------------------------------------------------------
+// 16 consecutive symbols of a chunk; positions past the tensor end read as "no symbol".
 __device__ __forceinline__ void load16(const uint16_t *__restrict__ sym, uint64_t i0, uint32_t numel,
                                        uint32_t s[16])
 {
@@ -161,60 +161,17 @@ __device__ __forceinline__ void load16(const uint16_t *__restrict__ sym, uint64_
     }
 }
 
-__global__ __launch_bounds__(kThreads) void k_chunk_bits(CompressArgs a)
-{
-    __shared__ __align__(16) uint8_t lens[kMaxSym];
-    __shared__ uint32_t wave_sum[kThreads / kWave];
-    const int tid = threadIdx.x;
-    for (int k = tid; k < (int)kMaxSym / 4; k += kThreads)
-        reinterpret_cast<uint32_t *>(lens)[k] = reinterpret_cast<const uint32_t *>(a.lens)[k];
-    __syncthreads();
-
-    const uint32_t c = blockIdx.x;
-    const uint64_t i0 = (uint64_t)c * kChunk + (uint64_t)tid * 16;
-    uint32_t s[16];
-    load16(a.sym, i0, a.numel, s);
-    uint32_t bits = 0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) bits += (s[j] != 0xffffffffu) ? lens[s[j]] : 0u;
-
-    // sub-block totals: `sub/16` consecutive lanes form one sub-block
-    const uint32_t group = a.sub / 16;              // 2, 4, 8 or 16
-    uint32_t g = bits;
-    for (uint32_t o = 1; o < group; o <<= 1) g += __shfl_xor(g, o);
-    if ((tid & (group - 1)) == 0) {
-        uint16_t *sub_bits = reinterpret_cast<uint16_t *>(a.out + a.lay.off_sub_bits);
-        sub_bits[(uint64_t)c * a.lay.nsub + tid / group] = (uint16_t)g;
-    }
-    uint32_t t = bits;
-    for (int o = 32; o > 0; o >>= 1) t += __shfl_down(t, o);
-    if ((tid & 63) == 0) wave_sum[tid >> 6] = t;
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t total = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
-        a.chunk_units[c] = (total + 127u) / 128u;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Exclusive scans of chunk sizes and outlier counts into the container, then the
-// header.  One workgroup of 1024 threads walks the chunks in slabs.
-// ---------------------------------------------------------------------------
-constexpr int kScanThreads = 1024;
-
+// exclusive prefix sum over the 256 threads of a workgroup (contains two barriers)
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t &total)
 {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    uint32_t inc = v;
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t n = __shfl_up(inc, o);
-        if (lane >= o) inc += n;
-    }
+    const uint32_t inc = wave_inclusive_sum(v);
     __syncthreads();                      // wave_tot may still be read from the previous call
     if (lane == 63) wave_tot[wv] = inc;
     __syncthreads();
     uint32_t base = 0, tot = 0;
-    for (int k = 0; k < (int)(blockDim.x >> 6); ++k) {
+#pragma unroll
+    for (int k = 0; k < kThreads / kWave; ++k) {
         const uint32_t t = wave_tot[k];
         if (k < wv) base += t;
         tot += t;
@@ -223,147 +180,363 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
     return base + inc - v;
 }
 
-__global__ __launch_bounds__(kScanThreads) void k_scan_header(CompressArgs a)
+__device__ __forceinline__ uint64_t desc_load(const uint64_t *p)
 {
-    __shared__ uint32_t wave_tot[kScanThreads / kWave];
-    const int tid = threadIdx.x;
-    const uint32_t nchunks = a.lay.nchunks;
-    uint32_t *chunk_off = reinterpret_cast<uint32_t *>(a.out + a.lay.off_chunk_off);
-    uint32_t *outl_off = reinterpret_cast<uint32_t *>(a.out + a.lay.off_outl_off);
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void desc_store(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-    uint64_t carry_units = 0;
-    uint32_t carry_outl = 0;
-    uint64_t bits_total = 0;
-    // entries nchunks .. pad4(nchunks+1)-1: the end marker and zero padding
-    const uint32_t padded = (nchunks + 1 + 3) & ~3u;
-    for (uint32_t base = 0; base < padded; base += kScanThreads) {
-        const uint32_t c = base + tid;
-        const uint32_t u = (c < nchunks) ? a.chunk_units[c] : 0u;
-        const uint32_t o = (c < nchunks) ? a.outl_cnt[c] : 0u;
-        uint32_t tu, to;
-        const uint32_t eu = block_exclusive_scan(u, wave_tot, tu);
-        const uint32_t eo = block_exclusive_scan(o, wave_tot, to);
-        if (c < padded) {
-            // offsets are u32 in the format; a payload of 2^32 units cannot occur below 2^32 codes
-            chunk_off[c] = (c <= nchunks) ? (uint32_t)(carry_units + eu) : 0u;
-            outl_off[c] = (c <= nchunks) ? carry_outl + eo : 0u;
+// Sum of a 62-bit descriptor value over the lanes selected by `take` (two 32-bit fields that
+// cannot carry into each other: units stay below 2^30, outliers below 2^32).
+__device__ __forceinline__ uint64_t wave_desc_sum(uint64_t d, bool take)
+{
+    const uint32_t lo = take ? (uint32_t)d : 0u, hi = take ? (uint32_t)((d & kDescMask) >> 32) : 0u;
+    const uint32_t slo = (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_sum(lo), 63);
+    const uint32_t shi = (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_sum(hi), 63);
+    return ((uint64_t)shi << 32) | slo;
+}
+
+constexpr uint32_t kSpinLimit = 1u << 22;          // polls before a look-back gives up
+
+// Exclusive prefix (units, outliers) of chunk c from the descriptors of its predecessors;
+// one wave, every lane inspects one predecessor per round (single-pass scan with look-back).
+// Chunks are handed out in index order, so every predecessor is owned by a workgroup that
+// is already running and publishes without waiting on anyone: the wait always ends.  The
+// poll limit only guards against a defect; on expiry *failed is set and 0 returned.
+__device__ __forceinline__ uint64_t look_back(const uint64_t *desc, uint32_t c, int lane, bool *failed)
+{
+    uint64_t excl = 0;
+    int64_t j = (int64_t)c - 1;                    // nearest predecessor not yet accounted for
+    uint32_t spins = 0;
+    while (j >= 0) {
+        const int64_t idx = j - lane;
+        const uint64_t d = (idx >= 0) ? desc_load(desc + idx) : kDescPrefix;   // before chunk 0: prefix 0
+        const uint32_t state = (uint32_t)(d >> 62);
+        const unsigned long long inv = __ballot(state == 0);
+        const unsigned long long pre = __ballot(state == 2);
+        const int first_inv = inv ? __ffsll((long long)inv) - 1 : 64;
+        const int first_pre = pre ? __ffsll((long long)pre) - 1 : 64;
+        if (first_pre < first_inv) {               // aggregates up to a published prefix: done
+            excl += wave_desc_sum(d, lane <= first_pre);
+            break;
         }
-        carry_units += tu;
-        carry_outl += to;
+        if (first_inv > 0) {                       // a run of aggregates: take them, look further back
+            excl += wave_desc_sum(d, lane < first_inv);
+            j -= first_inv;
+            continue;
+        }
+        if (++spins > kSpinLimit) { *failed = true; return 0; }
+        __builtin_amdgcn_s_sleep(2);
     }
-    // total_bits = sum of sub_bits (read back from the container section just written by k_chunk_bits)
-    {
-        const uint16_t *sub_bits = reinterpret_cast<const uint16_t *>(a.out + a.lay.off_sub_bits);
-        const uint64_t n = (uint64_t)nchunks * a.lay.nsub;
-        uint64_t acc = 0;
-        for (uint64_t k = tid; k < n; k += kScanThreads) acc += sub_bits[k];
-        for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o);
-        __shared__ uint64_t wave_bits[kScanThreads / kWave];
-        if ((tid & 63) == 0) wave_bits[tid >> 6] = acc;
-        __syncthreads();
-        if (tid == 0) for (int k = 0; k < kScanThreads / kWave; ++k) bits_total += wave_bits[k];
-    }
-    if (tid == 0) {
-        const uint64_t n_out = carry_outl;
-        const uint64_t off_outl_idx = a.lay.off_payload + carry_units * 16;
-        const uint64_t sect = (4 * n_out + 15) & ~15ull;
-        const uint64_t off_outl_val = off_outl_idx + sect;
-        const uint64_t total = off_outl_val + sect;
-        const bool fits = total <= a.out_cap;
-        Header hd;
-        uint32_t *raw = reinterpret_cast<uint32_t *>(&hd);
-        for (uint32_t k = 0; k < kHeaderBytes / 4; ++k) raw[k] = 0;
-        hd.magic = kMagic; hd.version = kVersion; hd.status = fits ? 0u : kStNoSpace;
-        hd.eb_bits = a.eb_bits;
-        for (int k = 0; k < 4; ++k) hd.shape[k] = a.shape[k];
-        hd.numel = a.numel;
-        hd.radius = a.radius; hd.chunk = kChunk; hd.sub = a.sub; hd.guard_shift = a.guard_shift;
-        hd.nchunks = nchunks; hd.n_outliers = (uint32_t)n_out;
-        hd.range_events = a.meta[kMetaRangeEvents]; hd.max_len = a.meta[kMetaMaxLen];
-        hd.total_bits = bits_total;
-        hd.off_lens = a.lay.off_lens; hd.off_chunk_off = a.lay.off_chunk_off;
-        hd.off_outl_off = a.lay.off_outl_off; hd.off_sub_bits = a.lay.off_sub_bits;
-        hd.off_payload = a.lay.off_payload; hd.off_outl_idx = off_outl_idx;
-        hd.off_outl_val = off_outl_val; hd.total_size = total;
-        uint32_t *dst = reinterpret_cast<uint32_t *>(a.out);
-        for (uint32_t k = 0; k < kHeaderBytes / 4; ++k) dst[k] = raw[k];
-        uint32_t st = 0;
-        if (!fits) st |= kStNoSpace;
-        if (hd.range_events) st |= kStRange;
-        if (st) atomicOr(a.status, st);
-        a.meta[kMetaSkip] = fits ? 0u : 1u;
-        a.meta[kMetaNOutliers] = (uint32_t)n_out;
-        a.meta[kMetaRangeEvents] = 0;          // ready for the next call
-    }
+    return excl;
 }
 
 // ---------------------------------------------------------------------------
-// Chunked Huffman bit-packing.  One workgroup per chunk: every thread packs its
-// 16 codewords at its bit offset into a zeroed LDS image of the chunk, which is
-// then copied out with 128-bit stores.  Bit k of the chunk is bit 31-(k%32) of
-// little-endian word k/32.
+// Sweep 2: chunked Huffman bit-packing with the bit offsets found on the fly.
+// Workgroups take tiles of up to 8 consecutive chunks in index order from a
+// ticket counter.  A tile's symbols are loaded once and stay in registers: first
+// their code lengths are summed (sub_bits, chunk sizes, the tile's size, which is
+// published at once), then each chunk is packed into a zeroed LDS image (bit k
+// of the chunk is bit 31-(k%32) of little-endian word k/32) and copied out with
+// 128-bit stores at the offset that wave 0 finds meanwhile by look-back.  The
+// workgroup that finishes last writes the header.
 // ---------------------------------------------------------------------------
 constexpr uint32_t kChunkImageWords = kChunk * kMaxCodeLen / 32;   // 6144 words = 24 KB
+constexpr int kTileMax = 8;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t row_shr(uint32_t x) { return dpp_u32<CTRL, 0xf>(x); }
+
+__device__ __forceinline__ uint32_t sym_at(const uint4 &lo, const uint4 &hi, int j)
+{
+    const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    const uint32_t v = w[j >> 1];
+    return (j & 1) ? (v >> 16) : (v & 0xffffu);
+}
+
+// Append one codeword (len <= 32) to the thread's bit accumulator and flush full 32-bit
+// words.  `acc` holds the bits of image word `wi` and the next one, left-aligned; `fill` < 32
+// counts the valid bits.
+__device__ __forceinline__ void append_bits(uint32_t *img, uint64_t &acc, uint32_t &fill, uint32_t &wi,
+                                            uint32_t code, uint32_t len)
+{
+    acc |= ((uint64_t)code) << ((64u - fill - len) & 63u);        // len == 0 adds nothing (code == 0)
+    fill += len;
+    if (fill >= 32) {
+        atomicOr(&img[wi], (uint32_t)(acc >> 32));
+        acc <<= 32; fill -= 32; ++wi;
+    }
+}
+
+// The symbols of a tile live in registers, chunk q in slot q.  The per-chunk loops below run
+// un-unrolled over slot 0 and rotate the slots after each chunk, so the loop body exists once
+// and register use stays bounded.
+struct TileRegs {
+    uint4    sv[kTileMax][2];        // 16 symbols per chunk (u16 pairs); 0xffff = past the end
+    uint32_t pos[kTileMax];          // this thread's bit offset inside each chunk
+    __device__ __forceinline__ void rotate()
+    {
+        const uint4 a0 = sv[0][0], a1 = sv[0][1];
+        const uint32_t p = pos[0];
+#pragma unroll
+        for (int q = 0; q + 1 < kTileMax; ++q) { sv[q][0] = sv[q + 1][0]; sv[q][1] = sv[q + 1][1]; pos[q] = pos[q + 1]; }
+        sv[kTileMax - 1][0] = a0; sv[kTileMax - 1][1] = a1; pos[kTileMax - 1] = p;
+    }
+};
+
+#ifdef CMPZ_PHASE_CLOCKS
+#define PHASE(k) if (tid == 0) { const long long now_ = clock64(); clk[k] += now_ - last_; last_ = now_; }
+#else
+#define PHASE(k)
+#endif
 
 __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
 {
-    __shared__ uint64_t codes[kMaxSym];
+#ifdef CMPZ_PHASE_CLOCKS
+    long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    long long last_ = clock64();
+#endif
+    __shared__ uint64_t table[kMaxSym];              // length << 56 | code
     __shared__ __align__(16) uint32_t image[kChunkImageWords];
-    __shared__ uint32_t wave_tot[kThreads / kWave];
-    if (a.meta[kMetaSkip]) return;
-    const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x;
-    const uint32_t *chunk_off = reinterpret_cast<const uint32_t *>(a.out + a.lay.off_chunk_off);
-    const uint32_t u0 = chunk_off[c], u1 = chunk_off[c + 1];
-    const uint32_t nwords = (u1 - u0) * 4;
-    if (u1 < u0 || nwords > kChunkImageWords) return;   // cannot happen for counts below 2^32
+    __shared__ uint32_t wave_bits[kThreads / kWave][kTileMax];
+    __shared__ uint32_t s_units[kTileMax];
+    __shared__ uint32_t s_tile;
+    __shared__ uint64_t s_excl;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const uint32_t nchunks = a.lay.nchunks, tc = a.tile_chunks;
+    const uint32_t ntiles = (nchunks + tc - 1) / tc;
+    uint32_t *chunk_off = reinterpret_cast<uint32_t *>(a.out + a.lay.off_chunk_off);
+    uint32_t *outl_off = reinterpret_cast<uint32_t *>(a.out + a.lay.off_outl_off);
+    uint16_t *sub_bits = reinterpret_cast<uint16_t *>(a.out + a.lay.off_sub_bits);
+    const uint32_t group = a.sub / 16;               // lanes per sub-block: 2, 4 or 8
+    const uint32_t *len_word = reinterpret_cast<const uint32_t *>(table) + 1;   // high words: length << 24 | ...
 
-    for (int k = tid; k < (int)kMaxSym; k += kThreads) codes[k] = a.codes[k];
-    for (uint32_t k = tid; k < nwords; k += kThreads) image[k] = 0;
+    for (int k = tid; k < (int)kMaxSym; k += kThreads) table[k] = a.codes[k];
+    uint64_t my_bits = 0;                            // thread 0: bits of the chunks this workgroup packed
+    bool failed = false;
+    TileRegs r;
 
-    const uint64_t i0 = (uint64_t)c * kChunk + (uint64_t)tid * 16;
-    uint32_t s[16];
-    load16(a.sym, i0, a.numel, s);
-    __syncthreads();
+    for (;;) {
+        __syncthreads();                             // previous round is done with the LDS state
+        if (tid == 0) s_tile = atomicAdd(&a.meta[kMetaTicket], 1u);
+        __syncthreads();
+        const uint32_t t = s_tile;
+        PHASE(0)
+        if (t >= ntiles) break;
+        const uint32_t c0 = t * tc;
+        const uint32_t nq = (nchunks - c0 < tc) ? nchunks - c0 : tc;     // chunks in this tile
 
-    uint64_t cw[16];
-    uint32_t bits = 0;
+        // ---- all symbols of the tile, issued together ----
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        cw[j] = (s[j] != 0xffffffffu) ? codes[s[j]] : 0ull;
-        bits += (uint32_t)(cw[j] >> 56);
-    }
-    uint32_t total;
-    uint32_t pos = block_exclusive_scan(bits, wave_tot, total);
-
-    // Append codewords MSB-first.  `acc` holds the bits of word `wi` and the next one,
-    // left-aligned; `fill` counts the valid bits in it.
-    uint32_t wi = pos >> 5;
-    uint32_t fill = pos & 31;
-    uint64_t acc = 0;
+        for (int q = 0; q < kTileMax; ++q) {
+            r.pos[q] = 0;
+            r.sv[q][0] = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
+            r.sv[q][1] = r.sv[q][0];
+            if (q < (int)nq) {
+                const uint64_t i0 = (uint64_t)(c0 + q) * kChunk + (uint64_t)tid * 16;
+                if (i0 + 16 <= a.numel) {
+                    r.sv[q][0] = *reinterpret_cast<const uint4 *>(a.sym + i0);
+                    r.sv[q][1] = *reinterpret_cast<const uint4 *>(a.sym + i0 + 8);
+                } else {
+                    uint32_t w[8];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        uint32_t len = (uint32_t)(cw[j] >> 56);
-        const uint64_t code = cw[j] & 0x00ffffffffffffffull;
-        if (len > 32) {                                     // rare: split off the high part
-            const uint32_t hl = len - 32;
-            acc |= (code >> 32) << (64 - fill - hl);
-            fill += hl;
-            if (fill >= 32) { atomicOr(&image[wi], (uint32_t)(acc >> 32)); acc <<= 32; fill -= 32; ++wi; }
-            len = 32;
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t lo = (i0 + 2 * j < a.numel) ? a.sym[i0 + 2 * j] : 0xffffu;
+                        const uint32_t hi = (i0 + 2 * j + 1 < a.numel) ? a.sym[i0 + 2 * j + 1] : 0xffffu;
+                        w[j] = lo | (hi << 16);
+                    }
+                    r.sv[q][0] = make_uint4(w[0], w[1], w[2], w[3]);
+                    r.sv[q][1] = make_uint4(w[4], w[5], w[6], w[7]);
+                }
+            }
         }
-        if (len) {
-            acc |= (code & 0xffffffffull) << (64 - fill - len);
-            fill += len;
-            if (fill >= 32) { atomicOr(&image[wi], (uint32_t)(acc >> 32)); acc <<= 32; fill -= 32; ++wi; }
+
+        PHASE(1)
+        // ---- code lengths: per-thread sums, sub-block sums, per-wave sums ----
+#pragma unroll 1
+        for (int q = 0; q < kTileMax; ++q) {
+            if (q < (int)nq) {
+                uint32_t bits = 0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const uint32_t sy = sym_at(r.sv[0][0], r.sv[0][1], j);
+                    bits += (sy != 0xffffu) ? (len_word[2 * sy] >> 24) : 0u;
+                }
+                const uint32_t inc = wave_inclusive_sum(bits);
+                const uint32_t exc = inc - bits;
+                // the first lane of a sub-block sits group-1 lanes below its last lane, in the same DPP row
+                const uint32_t first_exc = (group == 8) ? row_shr<0x117>(exc) : (group == 4) ? row_shr<0x113>(exc)
+                                                                                              : row_shr<0x111>(exc);
+                if ((tid & (group - 1)) == group - 1)
+                    sub_bits[(uint64_t)(c0 + q) * a.lay.nsub + tid / group] = (uint16_t)(inc - first_exc);
+                r.pos[0] = exc;                      // completed below with the lower waves' bits
+                if (lane == 63) wave_bits[wv][q] = inc;
+            }
+            r.rotate();
+        }
+        __syncthreads();
+        uint32_t tile_units = 0;
+#pragma unroll
+        for (int q = 0; q < kTileMax; ++q) {
+            if (q < (int)nq) {
+                uint32_t base = 0, tot = 0;
+#pragma unroll
+                for (int k = 0; k < kThreads / kWave; ++k) {
+                    const uint32_t w = wave_bits[k][q];
+                    if (k < wv) base += w;
+                    tot += w;
+                }
+                r.pos[q] += base;
+                const uint32_t u = (tot + 127u) / 128u;
+                tile_units += u;
+                if (tid == 0) { my_bits += tot; s_units[q] = u; }
+            }
+        }
+        PHASE(2)
+        // ---- publish the tile's size; wave 0 then finds the tile's offset by look-back ----
+        if (wv == 0) {
+            const uint32_t oc = (lane < (int)nq) ? a.outl_cnt[c0 + lane] : 0u;
+            const uint32_t oinc = wave_inclusive_sum(oc);
+            const uint32_t tile_outl = (uint32_t)__builtin_amdgcn_readlane((int)oinc, 63);
+            const uint64_t own = ((uint64_t)tile_units << 32) | tile_outl;
+            if (lane == 0) desc_store(a.desc + t, kDescAgg | own);
+            const uint64_t excl = look_back(a.desc, t, lane, &failed);
+            if (lane == 0) {
+                s_excl = excl;
+                // publish the inclusive prefix even after a failure so that successors do not wait
+                desc_store(a.desc + t, kDescPrefix | ((excl + own) & kDescMask));
+            }
+            if (lane < (int)nq) outl_off[c0 + lane] = (uint32_t)excl + oinc - oc;
+            if (c0 + nq == nchunks && lane == 0) {
+                // end markers, zero padding of both tables, and the totals for the header
+                const uint32_t padded = (nchunks + 1 + 3) & ~3u;
+                const uint32_t tot_u = (uint32_t)(excl >> 32) + tile_units, tot_o = (uint32_t)excl + tile_outl;
+                chunk_off[nchunks] = tot_u;
+                outl_off[nchunks] = tot_o;
+                for (uint32_t k = nchunks + 1; k < padded; ++k) { chunk_off[k] = 0; outl_off[k] = 0; }
+                a.meta[kMetaTotalUnits] = tot_u;
+                a.meta[kMetaNOutliers] = tot_o;
+            }
+        }
+
+        PHASE(3)
+        // ---- pack and store: consecutive chunks share the LDS image while they fit ----
+        constexpr uint32_t kImageUnits = kChunkImageWords / 4;
+        uint32_t u_img = 0;                          // units packed into the image and not yet stored
+        uint32_t u_done = 0;                         // units of the tile already stored
+        uint32_t left = tile_units;                  // units of the tile not yet packed
+        auto zero_image = [&]() {
+            const uint32_t nw = (left < kImageUnits ? left : kImageUnits) * 4;
+            for (uint32_t k = tid; k < nw; k += kThreads) image[k] = 0;
+        };
+        auto store_image = [&]() {                   // between two barriers issued by the caller
+            const uint32_t u0 = (uint32_t)(s_excl >> 32) + u_done;
+            const uint64_t end = a.lay.off_payload + ((uint64_t)u0 + u_img) * 16;
+            if (end <= a.out_cap) {
+                uint4 *dst = reinterpret_cast<uint4 *>(a.out + a.lay.off_payload + (uint64_t)u0 * 16);
+                const uint4 *src = reinterpret_cast<const uint4 *>(image);
+                for (uint32_t k = tid; k < u_img; k += kThreads) dst[k] = src[k];
+            }
+            u_done += u_img;
+            u_img = 0;
+        };
+        zero_image();
+        __syncthreads();                             // also makes s_units visible
+#pragma unroll 1
+        for (int q = 0; q < kTileMax; ++q) {
+            if (q < (int)nq) {                       // uniform
+                const uint32_t uq = s_units[q];
+                if (uq > kImageUnits) { failed = true; }              // cannot happen for counts below 2^32
+                else {
+                    if (u_img + uq > kImageUnits) {  // image full: store it and start afresh
+                        __syncthreads();
+                        store_image();
+                        __syncthreads();
+                        zero_image();
+                        __syncthreads();
+                    }
+                    if (tid == 0) chunk_off[c0 + q] = (uint32_t)(s_excl >> 32) + u_done + u_img;   // s_excl: see below
+                    const uint32_t p0 = u_img * 128u + r.pos[0];      // bit position in the image
+                    uint32_t wi = p0 >> 5, fill = p0 & 31;
+                    uint64_t acc = 0;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const uint32_t sy = sym_at(r.sv[0][0], r.sv[0][1], j);
+                        const uint64_t cw = (sy != 0xffffu) ? table[sy] : 0ull;
+                        uint32_t len = (uint32_t)(cw >> 56);
+                        if (len > 32) {                                 // rare: split off the high part
+                            append_bits(image, acc, fill, wi, (uint32_t)((cw & 0x00ffffffffffffffull) >> 32), len - 32);
+                            len = 32;
+                        }
+                        append_bits(image, acc, fill, wi, (uint32_t)cw, len);
+                    }
+                    if (fill && (uint32_t)(acc >> 32)) atomicOr(&image[wi], (uint32_t)(acc >> 32));
+                    u_img += uq;
+                    left -= uq;
+                }
+            }
+            r.rotate();
+        }
+        PHASE(4)
+        __syncthreads();                             // image complete
+        store_image();
+        PHASE(5)
+    }
+#ifdef CMPZ_PHASE_CLOCKS
+    if (tid == 0)
+        for (int k = 0; k < 8; ++k)
+            atomicAdd(reinterpret_cast<unsigned long long *>(a.meta + kMetaClocks) + 8 + k, (unsigned long long)clk[k]);
+#endif
+
+    // ---- the last workgroup to finish writes the header and re-arms the counters ----
+    if (tid == 0) {
+        unsigned long long *bits_acc = reinterpret_cast<unsigned long long *>(a.meta + kMetaBitsLo);
+        if (my_bits) atomicAdd(bits_acc, (unsigned long long)my_bits);
+        if (failed) atomicOr(a.status, kStInternal);
+        __threadfence();
+        const uint32_t done = atomicAdd(&a.meta[kMetaDone], 1u);
+        if (done == gridDim.x - 1) {
+            __threadfence();
+            const uint64_t total_units = __hip_atomic_load(&a.meta[kMetaTotalUnits], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t n_out = __hip_atomic_load(&a.meta[kMetaNOutliers], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t bits_total = __hip_atomic_load(bits_acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t range_events = __hip_atomic_load(&a.meta[kMetaRangeEvents], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t off_outl_idx = a.lay.off_payload + total_units * 16;
+            const uint64_t sect = (4 * n_out + 15) & ~15ull;
+            const uint64_t off_outl_val = off_outl_idx + sect;
+            const uint64_t total = off_outl_val + sect;
+            const bool fits = total <= a.out_cap;
+            Header hd;
+            uint32_t *raw = reinterpret_cast<uint32_t *>(&hd);
+            for (uint32_t k = 0; k < kHeaderBytes / 4; ++k) raw[k] = 0;
+            hd.magic = kMagic; hd.version = kVersion; hd.status = fits ? 0u : kStNoSpace;
+            hd.eb_bits = a.eb_bits;
+            for (int k = 0; k < 4; ++k) hd.shape[k] = a.shape[k];
+            hd.numel = a.numel;
+            hd.radius = a.radius; hd.chunk = kChunk; hd.sub = a.sub; hd.guard_shift = a.guard_shift;
+            hd.nchunks = nchunks; hd.n_outliers = (uint32_t)n_out;
+            hd.range_events = range_events; hd.max_len = a.meta[kMetaMaxLen];
+            hd.total_bits = bits_total;
+            hd.off_lens = a.lay.off_lens; hd.off_chunk_off = a.lay.off_chunk_off;
+            hd.off_outl_off = a.lay.off_outl_off; hd.off_sub_bits = a.lay.off_sub_bits;
+            hd.off_payload = a.lay.off_payload; hd.off_outl_idx = off_outl_idx;
+            hd.off_outl_val = off_outl_val; hd.total_size = total;
+            uint32_t *dst = reinterpret_cast<uint32_t *>(a.out);
+            for (uint32_t k = 0; k < kHeaderBytes / 4; ++k) dst[k] = raw[k];
+            uint32_t st = 0;
+            if (!fits) st |= kStNoSpace;
+            if (range_events) st |= kStRange;
+            if (st) atomicOr(a.status, st);
+            a.meta[kMetaSkip] = fits ? 0u : 1u;
+            a.meta[kMetaRangeEvents] = 0;          // ready for the next call
+            a.meta[kMetaTicket] = 0;
+            a.meta[kMetaDone] = 0;
+            *bits_acc = 0;
         }
     }
-    if (fill && (uint32_t)(acc >> 32)) atomicOr(&image[wi], (uint32_t)(acc >> 32));
-    __syncthreads();
-
-    uint4 *dst = reinterpret_cast<uint4 *>(a.out + a.lay.off_payload + (uint64_t)u0 * 16);
-    const uint4 *src = reinterpret_cast<const uint4 *>(image);
-    for (uint32_t k = tid; k < u1 - u0; k += kThreads) dst[k] = src[k];
 }
 
 // ---------------------------------------------------------------------------
@@ -441,9 +614,9 @@ void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st)
     const uint32_t tiles = (nchunks + kTileChunks - 1) / kTileChunks;
     launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist, dim3(tiles), dim3(kThreads), st, a);
     launch_codebook(a, prof, st);
-    launch(prof, kKChunkBits, k_chunk_bits, dim3(nchunks), dim3(kThreads), st, a);
-    launch(prof, kKScanHeader, k_scan_header, dim3(1), dim3(kScanThreads), st, a);
-    launch(prof, kKEncode, k_encode, dim3(nchunks), dim3(kThreads), st, a);
+    const uint32_t ntiles = (nchunks + a.tile_chunks - 1) / a.tile_chunks;
+    const uint32_t egrid = ntiles < 256u * 4u ? ntiles : 256u * 4u;
+    launch(prof, kKEncode, k_encode, dim3(egrid), dim3(kThreads), st, a);
     launch(prof, kKOutliers, k_outliers, dim3(nchunks), dim3(kThreads), st, a);
 }
 

@@ -30,7 +30,18 @@ __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, Decode
     __shared__ unsigned long long kraft_s;      // in units of 2^-56
     const int tid = threadIdx.x;
     const uint32_t nsym = 2 * a.radius;
-    const Header *hd = reinterpret_cast<const Header *>(a.buf);
+    // the header and the four table ends are fetched by separate lanes in one round trip
+    __shared__ Header hd_s;
+    __shared__ uint32_t ends_s[4];
+    if (tid < (int)(kHeaderBytes / 4)) reinterpret_cast<uint32_t *>(&hd_s)[tid] = reinterpret_cast<const uint32_t *>(a.buf)[tid];
+    if (tid >= 64 && tid < 68) {
+        const uint32_t *chunk_off = reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_chunk_off);
+        const uint32_t *outl_off = reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_outl_off);
+        const int k = tid - 64;
+        ends_s[k] = (k == 0) ? chunk_off[0] : (k == 1) ? chunk_off[a.lay.nchunks] : (k == 2) ? outl_off[0] : outl_off[a.lay.nchunks];
+    }
+    __syncthreads();
+    const Header *hd = &hd_s;
 
     if (tid == 0) {
         uint32_t bad = 0;
@@ -57,10 +68,8 @@ __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, Decode
             else if (((hd->off_outl_idx - l.off_payload) >> 4) >= (1ull << 32)) bad = kStFormat;
             if (!bad) {
                 const uint32_t units = (uint32_t)((hd->off_outl_idx - l.off_payload) >> 4);
-                const uint32_t *chunk_off = reinterpret_cast<const uint32_t *>(a.buf + l.off_chunk_off);
-                const uint32_t *outl_off = reinterpret_cast<const uint32_t *>(a.buf + l.off_outl_off);
-                if (chunk_off[0] != 0 || chunk_off[l.nchunks] != units) bad = kStFormat;
-                if (outl_off[0] != 0 || outl_off[l.nchunks] != (uint32_t)n_out) bad = kStFormat;
+                if (ends_s[0] != 0 || ends_s[1] != units) bad = kStFormat;
+                if (ends_s[2] != 0 || ends_s[3] != (uint32_t)n_out) bad = kStFormat;
                 T.payload_units = units;
                 T.n_outliers = (uint32_t)n_out;
             }

@@ -47,6 +47,13 @@ constexpr uint32_t kStRange    = 1u;
 constexpr uint32_t kStNoSpace  = 2u;
 constexpr uint32_t kStFormat   = 4u;
 constexpr uint32_t kStMismatch = 8u;
+constexpr uint32_t kStInternal = 16u;       // a bounded wait ran out (reported as CMP_E_HIP)
+
+// Tile descriptors of the encode sweep's single-pass scan: bits 63..62 state,
+// bits 61..32 payload units, bits 31..0 outlier count.  The first sweep leaves 0.
+constexpr uint64_t kDescAgg    = 1ull << 62;   // value = this tile alone
+constexpr uint64_t kDescPrefix = 2ull << 62;   // value = all tiles up to and including this one
+constexpr uint64_t kDescMask   = (1ull << 62) - 1;
 
 // Scratch words in ctx->d_meta.
 enum MetaWord : int {
@@ -55,6 +62,10 @@ enum MetaWord : int {
     kMetaSkip        = 2,   // nonzero: container does not fit, later kernels write nothing
     kMetaNOutliers   = 3,
     kMetaBad         = 4,   // decompress: nonzero when the container failed validation
+    kMetaTicket      = 5,   // next chunk to hand out in the encode sweep (zero between calls)
+    kMetaDone        = 6,   // workgroups of the encode sweep that have finished (zero between calls)
+    kMetaTotalUnits  = 7,   // payload size in 16-byte units
+    kMetaBitsLo      = 8,   // uint64 sum of codeword lengths (words 8 and 9; zero between calls)
     kMetaClocks      = 16,  // 24 uint64 phase-clock accumulators (only in CMPZ_PHASE_CLOCKS builds)
     kMetaWords       = 64
 };
@@ -74,8 +85,9 @@ struct CompressArgs {
     uint32_t *hist_copy;
     uint8_t  *lens;
     uint64_t *codes;        // len << 56 | code
-    uint32_t *chunk_units;  // payload size of each chunk in 16-byte units
+    uint64_t *desc;         // one descriptor per encode tile, see kDescAgg
     uint32_t *outl_cnt;     // outliers in each chunk
+    uint32_t  tile_chunks;  // chunks per encode tile: 1, 2, 4 or 8
     uint32_t *meta;
     uint32_t *status;
 };
