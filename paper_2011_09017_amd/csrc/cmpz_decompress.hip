@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecompressArgs a, const 
         uint32_t end = 0;
         if (nwords) {
             const uint32_t last = nwords - 1;
-            end = decode_run(T, [&](uint32_t k) -> uint32_t { return words[k < last ? k : last]; }, start, n_here, 0u, R,
+            end = decode_run<false>(T, [&](uint32_t k) -> uint32_t { return words[k < last ? k : last]; }, start, n_here, 0u, R,
                              [&](uint32_t k, uint32_t sy) { my[k] = (uint16_t)sy; }, bad);
         }
         if (end != start + sb) bad = true;
