@@ -32,9 +32,9 @@ HBM_PEAK_GBPS = 8000.0
 # measured): what the kernel must read and write once if nothing is re-read.
 KERNEL_BYTES = {
     "k_quant_lorenzo_split_hist": lambda cbar: 4.0 + 2.0,      # read x, write u16 symbols
-    "k_chunk_bits": lambda cbar: 2.0,                          # read symbols
-    "k_encode": lambda cbar: 2.0 + cbar,                       # read symbols, write payload
-    "k_decode": lambda cbar: cbar + 4.0,                       # read payload, write int32 residuals
+    "k_encode": lambda cbar: 2.0 + cbar,                       # read symbols, write container payload
+    "k_decode_fused": lambda cbar: cbar + 4.0,                 # read container, write fp32
+    "k_decode": lambda cbar: cbar + 4.0,                       # unfused path: read payload, write int32 residuals
     "k_row_scan": lambda cbar: 8.0,
     "k_col_scan_dequant": lambda cbar: 8.0,
 }
@@ -47,7 +47,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5_resnet18_stream")
     ap.add_argument("--eb", type=float, default=None)
-    ap.add_argument("--sub", type=int, default=128)
+    ap.add_argument("--sub", type=int, default=32, help="codes per sub-block (decode parallelism vs. 16 bits of metadata each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=2, help="tensors of the workload the oracle is timed on")
     args = ap.parse_args()

@@ -34,6 +34,24 @@
  *    q  = rint(x * r) clamped to [-16384, 16384], NaN -> 0           (compress)
  *    x' = (float)q * s                                               (decompress)
  * so that |x - x'| <= eb for every element whose |x * r| <= 16384.
+ *
+ * Container (little-endian; every section 16-byte aligned; padding bytes zero):
+ *    header, 256 bytes: +0 "CMPZ", +4 version u32 (1), +8 status u32 (0 = complete,
+ *      2 = did not fit), +12 eb bits u32, +16 shape u32[4], +32 numel u64,
+ *      +40 radius, +44 chunk, +48 sub, +52 guard_shift, +56 nchunks, +60 n_outliers,
+ *      +64 range_events, +68 max_len (all u32), +72 total_bits u64, then u64 offsets of
+ *      lens (+80), chunk_off (+88), outl_off (+96), sub_bits (+104), payload (+112),
+ *      outl_idx (+120), outl_val (+128), +136 total_size u64, rest zero
+ *    lens      u8[2*radius]          code length of each symbol (0 = unused); codes are
+ *                                    canonical: ordered by (length, symbol), first code 0,
+ *                                    read most significant bit first
+ *    chunk_off u32[nchunks+1]        start of each chunk's bit stream in 16-byte units
+ *    outl_off  u32[nchunks+1]        number of outliers before each chunk
+ *    sub_bits  u16[nchunks*chunk/sub] bits of every sub-block of `sub` consecutive codes
+ *    payload   chunk bit streams, each padded with zero bits to a multiple of 128 bits;
+ *              bit k of a stream is bit 31-(k%32) of little-endian 32-bit word k/32
+ *    outl_idx  u32[n_outliers]       linear NCHW index, ascending
+ *    outl_val  i32[n_outliers]       the Lorenzo residual kept verbatim
  */
 #ifndef CMPZ_H
 #define CMPZ_H

@@ -612,7 +612,8 @@ void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st)
     }
     const uint32_t nchunks = a.lay.nchunks;
     const uint32_t tiles = (nchunks + kTileChunks - 1) / kTileChunks;
-    launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist, dim3(tiles), dim3(kThreads), st, a);
+    if (!launch_sweep1_tiled(a, prof, st))
+        launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist, dim3(tiles), dim3(kThreads), st, a);
     launch_codebook(a, prof, st);
     const uint32_t ntiles = (nchunks + a.tile_chunks - 1) / a.tile_chunks;
     const uint32_t egrid = ntiles < 256u * 4u ? ntiles : 256u * 4u;

@@ -1,0 +1,193 @@
+// Sweep 1 of compression, LDS-tiled: pre-quantisation, 2D Lorenzo prediction,
+// quantisation-code / outlier split, histogram -- one read of x, one write of
+// the 16-bit symbols.
+//
+// The tensor is one linear array (element i has its neighbours at i-1, i-W and
+// i-W-1 of the same plane).  A workgroup takes chunks of 4096 consecutive
+// elements.  Phase A quantises the chunk and the W+1 elements before it once
+// each, with 128-bit loads, into an LDS array of int16 (|q| <= 16384).  Phase B
+// gives every thread 16 consecutive elements: residuals from the LDS values,
+// symbols, histogram (LDS-private, the zero residual counted per wave), two
+// 128-bit symbol stores.  Rows wider than the halo capacity take the untiled
+// kernel in cmpz_compress.hip.
+#include "cmpz_internal.h"
+
+namespace cmpz {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kHalo    = 1040;                    // LDS slots in front of the chunk; needs W + 4 <= kHalo
+constexpr int kQWords  = kHalo + (int)kChunk + 16;
+
+__device__ __forceinline__ int quant(float x, float r)
+{
+    float t = x * r;
+    if (!(fabsf(t) <= (float)kQMax)) t = (t != t) ? 0.0f : copysignf((float)kQMax, t);
+    return (int)__builtin_rintf(t);
+}
+__device__ __forceinline__ uint32_t clamps(float x, float r)
+{
+    const float t = x * r;
+    return (fabsf(t) <= (float)kQMax) ? 0u : 1u;
+}
+
+struct Sweep1Plan {
+    FastDiv  divW, divHW;
+    uint32_t chunks_per_wg;
+};
+
+__global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(CompressArgs a, Sweep1Plan pl)
+{
+    __shared__ __align__(16) int16_t Q[kQWords];
+    __shared__ uint32_t hist[kMaxSym];
+    __shared__ uint32_t ocnt;
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int k = tid; k < (int)kMaxSym; k += kThreads) hist[k] = 0;
+
+    const float *__restrict__ x = a.x;
+    const uint32_t numel = a.numel, W = a.W, H = a.H, HW = a.HW;
+    const int R = (int)a.radius;
+    const float r = a.r;
+    uint32_t events = 0, zero_run = 0;            // clamped elements; symbols equal to R seen by this thread
+
+    for (uint32_t t = 0; t < pl.chunks_per_wg; ++t) {
+        const uint32_t c = blockIdx.x * pl.chunks_per_wg + t;
+        if (c >= a.lay.nchunks) break;
+        const uint32_t t0 = c * kChunk;                              // first element of the chunk
+        const uint32_t t1 = (numel - t0 < kChunk) ? numel : t0 + kChunk;
+        __syncthreads();                                             // previous chunk's phase B is done with Q
+        if (tid == 0) ocnt = 0;
+
+        // ---- phase A: quantise [t0 - (W+1) rounded down to 4, t1) into Q ----
+        const uint32_t want = W + 1;
+        const uint32_t hs = (t0 >= want ? t0 - want : 0u) & ~3u;     // first element loaded
+        for (uint32_t g = hs + 4u * tid; g < t1; g += 4u * kThreads) {
+            float v[4];
+            if (g + 4 <= numel) {
+                const float4 f = *reinterpret_cast<const float4 *>(x + g);
+                v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = (g + j < numel) ? x[g + j] : 0.0f;
+            }
+            int q[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) q[j] = quant(v[j], r);
+            if (g >= t0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) events += (g + j < numel) ? clamps(v[j], r) : 0u;
+            }                                                        // (g and t0 are multiples of 4: no straddling)
+            uint2 pk;
+            pk.x = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
+            pk.y = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
+            // slot of element g: kHalo + (g - t0); g - t0 is a multiple of 4 (t0 and g are)
+            *reinterpret_cast<uint2 *>(&Q[(int)kHalo + (int)g - (int)t0]) = pk;
+        }
+        __syncthreads();
+
+        // ---- phase B: 16 consecutive elements per thread ----
+        const uint32_t i0 = 16u * tid;                               // chunk-local index of the first element
+        const uint32_t g0 = t0 + i0;
+        uint32_t s[16];
+        uint32_t nout = 0;
+        if (g0 < t1) {
+            // plane coordinates of the first element, then bit masks over the 16 elements:
+            // mw bit j = element j starts a row, mh bit j = element j lies in row 0 of its plane
+            const uint32_t p = pl.divHW.div(g0);
+            const uint32_t rem = g0 - p * HW;
+            uint32_t h = pl.divW.div(rem);
+            const uint32_t w = rem - h * W;
+            uint32_t mw = 0, mh = 0;
+            uint32_t j = w ? W - w : 0u;                             // first row start at or after element 0
+            if (h == 0 && j) mh |= (j >= 16u) ? 0xffffu : ((1u << j) - 1u);
+            if (w) h = (h + 1 == H) ? 0u : h + 1;                    // row index of that row start
+            for (; j < 16u; j += W) {
+                mw |= 1u << j;
+                if (h == 0) {
+                    const uint32_t e = j + W;
+                    mh |= ((e >= 16u) ? 0xffffu : ((1u << e) - 1u)) & ~((1u << j) - 1u);
+                }
+                h = (h + 1 == H) ? 0u : h + 1;
+            }
+            const int li = (int)kHalo + (int)i0;
+            int cur[17], up[17];                                     // index k holds element k-1
+            {
+                const uint4 a0 = *reinterpret_cast<const uint4 *>(&Q[li]);
+                const uint4 a1 = *reinterpret_cast<const uint4 *>(&Q[li + 8]);
+                const uint32_t wd[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    cur[1 + 2 * k] = (int)(int16_t)(wd[k] & 0xffffu);
+                    cur[2 + 2 * k] = (int)(int16_t)(wd[k] >> 16);
+                }
+                cur[0] = Q[li - 1];
+            }
+#pragma unroll
+            for (int k = 0; k < 17; ++k) up[k] = Q[li - (int)W - 1 + k];
+
+            const uint32_t nval = (t1 - g0 >= 16u) ? 16u : t1 - g0;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int keepw = ~__builtin_amdgcn_sbfe((int)mw, k, 1);     // 0 where the row starts
+                const int keeph = ~__builtin_amdgcn_sbfe((int)mh, k, 1);     // 0 in the first row
+                const int d = (cur[k + 1] - (cur[k] & keepw)) - ((up[k + 1] - (up[k] & keepw)) & keeph);
+                const uint32_t sy = (uint32_t)(d + R);
+                const bool in = (sy - 1u) < (uint32_t)(2 * R - 1);           // 1 <= d+R <= 2R-1
+                s[k] = in ? sy : 0u;
+                if ((uint32_t)k < nval) {
+                    nout += in ? 0u : 1u;
+                    if (s[k] == (uint32_t)R) ++zero_run;
+                    else atomicAdd(&hist[s[k]], 1u);
+                }
+            }
+            if (nval == 16u) {
+                uint4 o0, o1;
+                o0.x = s[0] | (s[1] << 16); o0.y = s[2] | (s[3] << 16); o0.z = s[4] | (s[5] << 16); o0.w = s[6] | (s[7] << 16);
+                o1.x = s[8] | (s[9] << 16); o1.y = s[10] | (s[11] << 16); o1.z = s[12] | (s[13] << 16); o1.w = s[14] | (s[15] << 16);
+                *reinterpret_cast<uint4 *>(a.sym + g0) = o0;
+                *reinterpret_cast<uint4 *>(a.sym + g0 + 8) = o1;
+            } else {
+                for (uint32_t k = 0; k < nval; ++k) a.sym[g0 + k] = (uint16_t)s[k];
+            }
+        }
+        if (nout) atomicAdd(&ocnt, nout);
+        __syncthreads();
+        if (tid == 0) {
+            a.outl_cnt[c] = ocnt;
+            if (c % a.tile_chunks == 0) a.desc[c / a.tile_chunks] = 0;       // re-arm the encode sweep's scan
+        }
+    }
+
+    // zero residuals: one LDS atomic per wave
+    {
+        const uint32_t tot = wave_inclusive_sum(zero_run);
+        if (lane == 63 && tot) atomicAdd(&hist[R], tot);
+    }
+    __syncthreads();
+    for (int k = tid; k < (int)kMaxSym; k += kThreads) {
+        const uint32_t n = hist[k];
+        if (n) atomicAdd(&a.hist[k], n);
+    }
+    {
+        const uint32_t tot = wave_inclusive_sum(events);
+        if (lane == 63 && tot) atomicAdd(&a.meta[kMetaRangeEvents], tot);
+    }
+}
+
+}  // namespace
+
+// Returns false when rows are too wide for the halo (caller uses the untiled kernel).
+bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st)
+{
+    if (a.W + 4 > (uint32_t)kHalo) return false;
+    Sweep1Plan pl;
+    pl.divW = FastDiv::make(a.W);
+    pl.divHW = FastDiv::make(a.HW);
+    pl.chunks_per_wg = 8;
+    while (pl.chunks_per_wg > 1 && (a.lay.nchunks + pl.chunks_per_wg - 1) / pl.chunks_per_wg < 2048) pl.chunks_per_wg >>= 1;
+    const uint32_t grid = (a.lay.nchunks + pl.chunks_per_wg - 1) / pl.chunks_per_wg;
+    launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist_tiled, dim3(grid), dim3(kThreads), st, a, pl);
+    return true;
+}
+
+}  // namespace cmpz
