@@ -141,7 +141,7 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     uint64_t off = 0;
     auto carve = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, 256); return o; };
     const uint64_t o_sym = carve(2 * (c.max_numel + 16));
-    const uint64_t o_hist = carve(4 * kMaxSym);
+    const uint64_t o_hist = carve(4 * kMaxSym * kHistCopies);
     const uint64_t o_hist_copy = carve(4 * kMaxSym);
     const uint64_t o_desc = carve(8 * (ctx->max_chunks + 1));
     const uint64_t o_ocnt = carve(4 * (ctx->max_chunks + 1));
@@ -221,9 +221,10 @@ int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float e
     a.sym = ctx->d_sym; a.hist = ctx->d_hist; a.hist_copy = ctx->d_hist_copy;
     a.lens = ctx->d_lens; a.codes = ctx->d_codes;
     a.desc = ctx->d_desc; a.outl_cnt = ctx->d_outl_cnt;
-    // encode tiles: as large as still leaves a few thousand of them to spread over the chip
+    // encode tiles: every tile costs one ticket (a serialised atomic), so as large as still
+    // leaves several hundred of them to spread over the chip
     a.tile_chunks = 8;
-    while (a.tile_chunks > 1 && (a.lay.nchunks + a.tile_chunks - 1) / a.tile_chunks < 2048) a.tile_chunks >>= 1;
+    while (a.tile_chunks > 1 && (a.lay.nchunks + a.tile_chunks - 1) / a.tile_chunks < 768) a.tile_chunks >>= 1;
     a.meta = ctx->d_meta; a.status = ctx->d_status;
 
     DeviceGuard guard(ctx->device);

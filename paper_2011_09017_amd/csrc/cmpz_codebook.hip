@@ -48,8 +48,11 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
 
     // 1. fetch the histogram, leave it zeroed for the next call, keep a copy for inspection
     uint32_t cnt = 0;
-    if ((uint32_t)tid < nsym) cnt = a.hist[tid];
-    a.hist[tid] = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < kHistCopies; ++k) {
+        if ((uint32_t)tid < nsym) cnt += a.hist[k * kMaxSym + tid];
+        a.hist[k * kMaxSym + tid] = 0;
+    }
     a.hist_copy[tid] = cnt;
     len_of[tid] = 0;
     if (tid < 64) { bl_count[tid] = 0; first_code[tid] = 0; }

@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist(CompressA
     __syncthreads();
     for (int k = tid; k < (int)kMaxSym; k += kThreads) {
         const uint32_t c = hist[k];
-        if (c) atomicAdd(&a.hist[k], c);
+        if (c) atomicAdd(&a.hist[(blockIdx.x % kHistCopies) * kMaxSym + k], c);
     }
     if (tid < kTileChunks) {
         const uint64_t c = (uint64_t)blockIdx.x * kTileChunks + tid;

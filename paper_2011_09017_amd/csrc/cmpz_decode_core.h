@@ -43,6 +43,206 @@ __device__ __forceinline__ void load_tables(DecodeTables &dst, const DecodeTable
     for (uint32_t k = tid; k < sizeof(DecodeTables) / 4; k += nthreads) d[k] = s[k];
 }
 
+// Validation of the container header and code lengths, and construction of the decode tables
+// in LDS, by one workgroup of 256 threads (every workgroup of the fused decode kernel does this
+// for itself: about a microsecond, and no separate kernel or round trip through memory).
+// `scratch` is LDS the caller does not need yet (at least 12 KB).  Returns 0 or the status bits
+// of the defect found; contains barriers, so all 256 threads must call it.
+//
+// Canonical codes are ascending in (length, symbol) when left-aligned, so with
+//   s[l] = count[l] << (48 - l)  and  P[l] = sum of s[j] over 1 <= j < l
+// the first code of length l is P[l] >> (48 - l), the code is complete iff the total is 2^48,
+// and a left-aligned value v belongs to the shortest length l with v < P[l+1].
+__device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const DecompressArgs &a, uint32_t *scratch)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    Header *hd = reinterpret_cast<Header *>(scratch);                 // 64 words
+    uint32_t *ends = scratch + 64;                                    // 4 words
+    uint32_t *bad_s = scratch + 68, *bad2_s = scratch + 69;       // defects found before / after the second barrier
+    uint64_t *lim = reinterpret_cast<uint64_t *>(scratch + 72);       // 64 x u64: P[l+1], units of 2^-48
+    uint32_t (*wave_cnt)[64] = reinterpret_cast<uint32_t (*)[64]>(scratch + 200);   // 16 x 64: [pass*4 + wave][length]
+    const uint32_t nsym = 2 * a.radius;
+
+    if (tid < (int)(kHeaderBytes / 4)) {
+        const uint32_t v = reinterpret_cast<const uint32_t *>(a.buf)[tid];
+        scratch[tid] = v;
+    }
+    if (tid >= 64 && tid < 68) {
+        const uint32_t *chunk_off = reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_chunk_off);
+        const uint32_t *outl_off = reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_outl_off);
+        const int k = tid - 64;
+        ends[k] = (k == 0) ? chunk_off[0] : (k == 1) ? chunk_off[a.lay.nchunks] : (k == 2) ? outl_off[0] : outl_off[a.lay.nchunks];
+    }
+    if (tid == 68) { *bad_s = 0; *bad2_s = 0; }
+    for (int k = tid; k < 16 * 64; k += 256) (&wave_cnt[0][0])[k] = 0;
+    // code lengths, 4 symbols per thread (symbol q*256 + tid), fetched while the header arrives
+    const uint32_t padded = (nsym + 15u) & ~15u;
+    uint32_t L[4];
+    bool bad_len = false;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t k = q * 256u + tid;
+        uint32_t v = 0;
+        if (k < padded) v = a.buf[a.lay.off_lens + k];
+        if ((k >= nsym && v) || v > kMaxCodeLen) { bad_len = true; v = 0; }
+        L[q] = v;
+    }
+    __syncthreads();
+    {
+        // the reserved tail of the header must be zero
+        constexpr int kFirstZero = (int)(offsetof(Header, zero) / 4);
+        bool nz = false;
+        if (tid >= kFirstZero && tid < (int)(kHeaderBytes / 4)) nz = scratch[tid] != 0;
+        if (nz || bad_len) atomicOr(bad_s, kStFormat);
+    }
+    if (tid == 0) {
+        uint32_t bad = 0;
+        const Layout &l = a.lay;
+        if (hd->magic != kMagic || hd->version != kVersion || hd->status != 0) bad = kStFormat;
+        if (!bad) {
+            if (hd->eb_bits != a.eb_bits) bad = kStMismatch;
+            for (int k = 0; k < 4; ++k) if (hd->shape[k] != a.shape[k]) bad = kStMismatch;
+            if (hd->radius != a.radius || hd->chunk != kChunk || hd->sub != a.sub ||
+                hd->guard_shift != a.guard_shift) bad = kStMismatch;
+        }
+        if (!bad) {
+            const uint64_t n_out = hd->n_outliers;
+            const uint64_t sect = (4 * n_out + 15) & ~15ull;
+            if (hd->numel != a.numel || hd->nchunks != l.nchunks) bad = kStFormat;
+            else if (hd->off_lens != l.off_lens || hd->off_chunk_off != l.off_chunk_off ||
+                     hd->off_outl_off != l.off_outl_off || hd->off_sub_bits != l.off_sub_bits ||
+                     hd->off_payload != l.off_payload) bad = kStFormat;
+            else if (hd->total_size > a.size || n_out > a.numel || hd->range_events > a.numel) bad = kStFormat;
+            else if (hd->off_outl_idx < l.off_payload || ((hd->off_outl_idx - l.off_payload) & 15)) bad = kStFormat;
+            else if (hd->off_outl_val != hd->off_outl_idx + sect || hd->total_size != hd->off_outl_val + sect)
+                bad = kStFormat;
+            else if (((hd->off_outl_idx - l.off_payload) >> 4) >= (1ull << 32)) bad = kStFormat;
+            if (!bad) {
+                const uint32_t units = (uint32_t)((hd->off_outl_idx - l.off_payload) >> 4);
+                if (ends[0] != 0 || ends[1] != units) bad = kStFormat;
+                if (ends[2] != 0 || ends[3] != (uint32_t)n_out) bad = kStFormat;
+                T.payload_units = units;
+                T.n_outliers = (uint32_t)n_out;
+            }
+        }
+        if (bad) atomicOr(bad_s, bad);
+    }
+    // rank of every symbol among the symbols of its length in its wave and pass
+    uint32_t in_wave[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t Lq = L[q];
+        uint32_t r = 0;
+        unsigned long long remaining = __ballot(Lq != 0);
+        while (remaining) {                                   // wave-uniform
+            const int leader = __ffsll((long long)remaining) - 1;
+            const uint32_t Lx = (uint32_t)__builtin_amdgcn_readlane((int)Lq, leader);
+            const unsigned long long m = __ballot(Lq == Lx);
+            if (Lq == Lx) r = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            if (lane == leader) wave_cnt[q * 4 + wv][Lx] = (uint32_t)__popcll(m);
+            remaining &= ~m;
+        }
+        in_wave[q] = r;
+    }
+    __syncthreads();
+    if (*bad_s) return *bad_s;
+
+    // wave 0, lane = length: totals per length, start of every (pass, wave) group, first codes
+    if (wv == 0) {
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const uint32_t c = wave_cnt[k][lane];
+            wave_cnt[k][lane] = cnt;                          // symbols of this length in earlier groups
+            cnt += c;
+        }
+        if (lane == 0) cnt = 0;
+        const uint32_t used = (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_sum(cnt), 63);
+        const uint32_t offs = wave_inclusive_sum(cnt) - cnt;
+        const unsigned long long present = __ballot(cnt != 0);
+        const uint32_t max_len = present ? 63u - (uint32_t)__builtin_clzll(present) : 0u;
+        // s < 2^58: three limbs of 24 bits, each scanned in 32 bits without overflow
+        const uint64_t sl = (lane >= 1 && lane <= (int)kMaxCodeLen) ? ((uint64_t)cnt << (kMaxCodeLen - lane)) : 0ull;
+        const uint32_t i0 = wave_inclusive_sum((uint32_t)(sl & 0xffffffu));
+        const uint32_t i1 = wave_inclusive_sum((uint32_t)((sl >> 24) & 0xffffffu));
+        const uint32_t i2 = wave_inclusive_sum((uint32_t)(sl >> 48));
+        const uint64_t incl = (uint64_t)i0 + ((uint64_t)i1 << 24) + ((uint64_t)i2 << 48);
+        const uint64_t excl = incl - sl;
+        const uint64_t first = (lane >= 1 && lane <= (int)kMaxCodeLen) ? (excl >> (kMaxCodeLen - lane)) : 0ull;
+        T.first[lane] = first; T.count[lane] = cnt; T.offs[lane] = offs;
+        lim[lane] = incl;
+        if (lane == 63) {
+            uint32_t bad = 0;
+            const uint64_t one = 1ull << kMaxCodeLen;
+            if (used >= 2 && incl != one) bad = kStFormat;
+            if (used == 1 && max_len != 1) bad = kStFormat;
+            if (used == 0 && a.numel != 0) bad = kStFormat;
+            if (hd->max_len != max_len) bad = kStFormat;
+            if (bad) *bad2_s = bad;
+            T.max_len = max_len;
+        }
+        if (lane == (int)kLB) {
+            // codes longer than kLB bits occupy left-aligned 32-bit values [t32, 2^32)
+            const uint64_t t = incl >> (kMaxCodeLen - 32);
+            const uint64_t span = (1ull << 32) - (t < (1ull << 32) ? t : (1ull << 32));
+            uint32_t sh = 0;
+            while ((span >> sh) > kT2Size) ++sh;
+            T.t32 = (uint32_t)t; T.sh = sh; T.has_long = (max_len > kLB && span > 0) ? 1u : 0u;
+        }
+    }
+    __syncthreads();
+    if (*bad2_s) return *bad2_s;
+
+    // symbols ordered by (length, symbol)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (L[q]) T.sorted[T.offs[L[q]] + wave_cnt[q * 4 + wv][L[q]] + in_wave[q]] = (uint16_t)(q * 256 + tid);
+    __syncthreads();
+
+    // level 1: entry idx is the codeword (if any, of at most kLB bits) that prefixes idx
+    {
+        uint32_t l1[kLB + 1];
+#pragma unroll
+        for (uint32_t l = 1; l <= kLB; ++l) {
+            const uint64_t v = lim[l] >> (kMaxCodeLen - kLB);
+            l1[l] = v > kT1Size ? kT1Size : (uint32_t)v;
+        }
+#pragma unroll 2
+        for (uint32_t idx = tid; idx < kT1Size; idx += 256) {
+            uint32_t l = 1;
+#pragma unroll
+            for (uint32_t k = 1; k <= kLB; ++k) l += (idx >= l1[k]) ? 1u : 0u;
+            uint32_t e = 0;
+            if (l <= kLB) e = T.sorted[T.offs[l] + (idx >> (kLB - l)) - (uint32_t)T.first[l]] | (l << 10);
+            T.t1[idx] = (uint16_t)e;
+        }
+    }
+    // level 2: entry i covers left-aligned 32-bit values t32 + [i << sh, (i+1) << sh); it holds a
+    // codeword only if the whole entry lies inside it (length at most 32 - sh)
+    {
+        const uint32_t sh = T.sh, t32 = T.t32, has_long = T.has_long;
+        const uint32_t lmax = (32 - sh < T.max_len) ? 32 - sh : T.max_len;
+        uint64_t v[4];
+        uint32_t l[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[k] = (uint64_t)t32 + ((uint64_t)(tid + 256 * k) << sh); l[k] = kLB + 1; }
+        for (uint32_t j = kLB + 1; j <= lmax; ++j) {          // uniform
+            const uint64_t lj = lim[j] >> (kMaxCodeLen - 32);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) l[k] += (v[k] >= lj) ? 1u : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t e = 0;
+            if (has_long && v[k] < (1ull << 32) && l[k] <= lmax)
+                e = T.sorted[T.offs[l[k]] + (uint32_t)((v[k] >> (32 - l[k])) - T.first[l[k]])] | (l[k] << 10);
+            T.t2[tid + 256 * k] = (uint16_t)e;
+        }
+    }
+    __syncthreads();
+    return 0;
+}
+
 // Decode `count` codewords that start at bit `start` of a chunk stream whose 32-bit words
 // are read through rd(word index); rd must be safe for any index (clamp) -- words past the
 // stream only ever reach bits that a well-formed stream does not consume.  put(k, symbol) is

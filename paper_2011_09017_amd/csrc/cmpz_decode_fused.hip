@@ -56,8 +56,7 @@ struct Ahead {
 };
 
 template <int SUB>
-__global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, const DecodeTables *__restrict__ tb,
-                                                           FusedPlan pl)
+__global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, FusedPlan pl)
 {
     constexpr int kLog  = Cfg<SUB>::kLog;
     constexpr int kNDec = kBandMax / SUB;                 // decode lanes per band
@@ -72,14 +71,19 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, con
     __shared__ uint32_t lane_reset[kNDec];                // offset of the lane's first row start (SUB = none)
     __shared__ int32_t  lane_carry[kNDec];                // what the lane's elements before that offset lack
 
-    if (a.meta[kMetaBad]) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
 #ifdef CMPZ_PHASE_CLOCKS
     long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = clock64();
 #endif
-    load_tables(T, tb, tid, kThreads);
-    __syncthreads();
+    // every workgroup validates the container and builds the decode tables for itself
+    {
+        const uint32_t defect = build_tables_256(T, a, reinterpret_cast<uint32_t *>(R));
+        if (defect) {
+            if (blockIdx.x == 0 && tid == 0) atomicOr(a.status, defect);
+            return;
+        }
+    }
     PHASE(0)
     const uint32_t payload_units = T.payload_units, n_outl = T.n_outliers;
 
@@ -374,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, con
 }  // namespace
 
 // Returns false when the shape does not fit the fused kernel (caller falls back).
-bool launch_decode_fused(const DecompressArgs &a, const DecodeTables *tb, Profiler *prof, hipStream_t st)
+bool launch_decode_fused(const DecompressArgs &a, Profiler *prof, hipStream_t st)
 {
     const uint32_t ndec = kBandMax / a.sub;
     const uint64_t cap = (uint64_t)(ndec - 1) * a.sub + 1;     // a band then spans at most ndec sub-blocks
@@ -391,9 +395,9 @@ bool launch_decode_fused(const DecompressArgs &a, const DecodeTables *tb, Profil
     }
     const uint32_t grid = pl.nitems < 256u * 8u ? pl.nitems : 256u * 8u;
     switch (a.sub) {
-    case 32:  launch(prof, kKDecodeFused, k_decode_fused<32>, dim3(grid), dim3(kThreads), st, a, tb, pl); break;
-    case 64:  launch(prof, kKDecodeFused, k_decode_fused<64>, dim3(grid), dim3(kThreads), st, a, tb, pl); break;
-    default:  launch(prof, kKDecodeFused, k_decode_fused<128>, dim3(grid), dim3(kThreads), st, a, tb, pl); break;
+    case 32:  launch(prof, kKDecodeFused, k_decode_fused<32>, dim3(grid), dim3(kThreads), st, a, pl); break;
+    case 64:  launch(prof, kKDecodeFused, k_decode_fused<64>, dim3(grid), dim3(kThreads), st, a, pl); break;
+    default:  launch(prof, kKDecodeFused, k_decode_fused<128>, dim3(grid), dim3(kThreads), st, a, pl); break;
     }
     return true;
 }

@@ -291,11 +291,11 @@ size_t decode_tables_bytes() { return sizeof(DecodeTables); }
 
 void launch_decompress(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st)
 {
+    if (a.numel != 0 && launch_decode_fused(a, prof, st)) return;
     DecodeTables *tb = static_cast<DecodeTables *>(tables);
     launch(prof, kKDecodeTables, k_decode_tables, dim3(1), dim3(1024), st, a, tb);
     if (a.numel == 0) return;
     const DecodeTables *ctb = tb;
-    if (launch_decode_fused(a, ctb, prof, st)) return;
     // shapes the fused kernel does not take: residuals staged in the output buffer
     const uint64_t nsubs = (uint64_t)a.lay.nchunks * a.lay.nsub;
     const uint32_t blocks = (uint32_t)((nsubs + kDecThreads - 1) / kDecThreads);

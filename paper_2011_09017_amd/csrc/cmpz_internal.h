@@ -16,6 +16,7 @@ constexpr int      kQMax        = 16384;    // clamp of the pre-quantised intege
 constexpr uint32_t kHeaderBytes = 256;
 constexpr uint32_t kMaxCodeLen  = 48;       // counts below 2^32 bound a Huffman depth by 45
 constexpr uint32_t kVersion     = 1;
+constexpr uint32_t kHistCopies  = 8;        // global histogram replicas that workgroups flush into (less contention)
 
 // Container header, little-endian, 256 bytes; bytes 144..255 are zero.
 struct Header {
@@ -232,6 +233,6 @@ void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st);
 bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st);
 size_t decode_tables_bytes();
 void launch_decompress(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st);
-bool launch_decode_fused(const DecompressArgs &a, const DecodeTables *tb, Profiler *prof, hipStream_t st);
+bool launch_decode_fused(const DecompressArgs &a, Profiler *prof, hipStream_t st);
 
 }  // namespace cmpz

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Com
     __syncthreads();
     for (int k = tid; k < (int)kMaxSym; k += kThreads) {
         const uint32_t n = hist[k];
-        if (n) atomicAdd(&a.hist[k], n);
+        if (n) atomicAdd(&a.hist[(blockIdx.x % kHistCopies) * kMaxSym + k], n);
     }
     {
         const uint32_t tot = wave_inclusive_sum(events);
@@ -183,8 +183,10 @@ bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st)
     Sweep1Plan pl;
     pl.divW = FastDiv::make(a.W);
     pl.divHW = FastDiv::make(a.HW);
-    pl.chunks_per_wg = 8;
-    while (pl.chunks_per_wg > 1 && (a.lay.nchunks + pl.chunks_per_wg - 1) / pl.chunks_per_wg < 2048) pl.chunks_per_wg >>= 1;
+    // every workgroup ends with a flush of its histogram (contended atomics): few, long-lived
+    // workgroups, but still a few per CU
+    pl.chunks_per_wg = (a.lay.nchunks + 1535) / 1536;
+    if (pl.chunks_per_wg < 1) pl.chunks_per_wg = 1;
     const uint32_t grid = (a.lay.nchunks + pl.chunks_per_wg - 1) / pl.chunks_per_wg;
     launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist_tiled, dim3(grid), dim3(kThreads), st, a, pl);
     return true;
