@@ -3,9 +3,13 @@
 
 A step = one pass of the whole path over one batch of synthetic activations:
 every tensor of the workload is compressed in forward order, then every
-container is decompressed in reverse order, all on one stream (the forward /
-backward pattern of Section 4.4 of the paper).  Inputs are resident in HBM
-before the timed region starts.  Prints ONE JSON line.
+container is decompressed in reverse order (the forward / backward pattern of
+Section 4.4 of the paper).  Tensor i is handled by context i mod S on stream
+i mod S (--streams S): tensors are independent, so the serial parts of one
+tensor's codec (codebook construction, kernel tails) overlap with the bulk
+kernels of its neighbours, as they overlap with the layers' own kernels in
+training.  Inputs are resident in HBM before the timed region starts.  Prints
+ONE JSON line.
 
   value      = fp32 bytes compressed + fp32 bytes decompressed, per second (GB/s)
   roofline   = the kernel with the largest share of the step: its algorithmic
@@ -48,6 +52,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg5_resnet18_stream")
     ap.add_argument("--eb", type=float, default=None)
     ap.add_argument("--sub", type=int, default=32, help="codes per sub-block (decode parallelism vs. 16 bits of metadata each)")
+    ap.add_argument("--streams", type=int, default=2, help="contexts/streams the tensors are dealt over, round robin")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=2, help="tensors of the workload the oracle is timed on")
     args = ap.parse_args()
@@ -70,21 +75,28 @@ def main() -> int:
     xs = [wl.tensor(i, device=dev) for i in range(len(wl.shapes))]
     numels = [x.numel() for x in xs]
     total = sum(numels)
-    ctx = binding.Context(sub=args.sub, max_numel=max(numels))
-    bounds = [ctx.bound(x.shape) for x in xs]
+    S = max(1, min(args.streams, len(xs)))
+    ctxs = [binding.Context(sub=args.sub, max_numel=max(numels[k::S])) for k in range(S)]
+    bounds = [ctxs[0].bound(x.shape) for x in xs]
     arena = [torch.empty(b, dtype=torch.uint8, device=dev) for b in bounds]
     outs = [torch.empty_like(x) for x in xs]
-    stream = torch.cuda.current_stream(dev).cuda_stream
-    h = ctx._h
+    # default-priority streams; with one stream, torch's current one
+    tstreams = [torch.cuda.current_stream(dev)] if S == 1 else [torch.cuda.Stream(dev) for _ in range(S)]
+    streams = [t.cuda_stream for t in tstreams]
+    order = list(range(len(xs)))
 
     def compress_all():
-        for x, buf in zip(xs, arena):
-            rc, _ = binding.cmp_compress(h, x.data_ptr(), x.shape, eb, buf.data_ptr(), buf.numel(), False, stream)
+        for i in order:
+            x, buf = xs[i], arena[i]
+            rc, _ = binding.cmp_compress(ctxs[i % S]._h, x.data_ptr(), x.shape, eb, buf.data_ptr(), buf.numel(),
+                                         False, streams[i % S])
             assert rc == 0, binding.cmp_strerror(rc)
 
     def decompress_all():
-        for x, buf, out, cap in zip(reversed(xs), reversed(arena), reversed(outs), reversed(bounds)):
-            rc = binding.cmp_decompress(h, buf.data_ptr(), cap, x.shape, eb, out.data_ptr(), stream)
+        for i in reversed(order):
+            x = xs[i]
+            rc = binding.cmp_decompress(ctxs[i % S]._h, arena[i].data_ptr(), bounds[i], x.shape, eb,
+                                        outs[i].data_ptr(), streams[i % S])
             assert rc == 0, binding.cmp_strerror(rc)
 
     def step():
@@ -94,11 +106,12 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    st = ctx.last_status()
-    assert st == 0, binding.cmp_strerror(st)
+    for k in range(S):
+        st = ctxs[k].last_status(streams[k])
+        assert st == 0, binding.cmp_strerror(st)
     sizes = []
     for buf in arena:
-        rc, size = ctx.compressed_size(buf)
+        rc, size = ctxs[0].compressed_size(buf)
         assert rc == 0
         sizes.append(size)
     comp_bytes = sum(sizes)
@@ -119,25 +132,28 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    # per-phase times with events on the same stream
-    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    # per-phase times (host clock, a device-wide wait after each phase)
     tc = td = 0.0
     for _ in range(args.steps):
-        e[0].record(); compress_all(); e[1].record(); decompress_all(); e[2].record()
-        torch.cuda.synchronize()
-        tc += e[0].elapsed_time(e[1]); td += e[1].elapsed_time(e[2])
+        a = time.perf_counter(); compress_all(); torch.cuda.synchronize()
+        b = time.perf_counter(); decompress_all(); torch.cuda.synchronize()
+        c = time.perf_counter()
+        tc += (b - a) * 1e3; td += (c - b) * 1e3
     tc /= args.steps; td /= args.steps
 
     # ---- per-kernel durations (events around every launch), same K steps ----------------
-    ctx.profile(True)
+    for c in ctxs:
+        c.profile(True)
     for _ in range(args.steps):
         step()
-    prof = ctx.profile_read()
-    ctx.profile(False)
     kern = {}
-    for name, (ms, launches) in prof.items():
-        kern[name] = {"ms_per_step": ms / args.steps, "launches_per_step": launches // args.steps,
-                      "avg_us": 1e3 * ms / launches}
+    for k, c in enumerate(ctxs):
+        for name, (ms, launches) in c.profile_read(streams[k]).items():
+            e = kern.setdefault(name, {"ms": 0.0, "launches": 0})
+            e["ms"] += ms; e["launches"] += launches
+        c.profile(False)
+    kern = {name: {"ms_per_step": e["ms"] / args.steps, "launches_per_step": e["launches"] // args.steps,
+                   "avg_us": 1e3 * e["ms"] / e["launches"]} for name, e in kern.items()}
     dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
     bytes_fn = KERNEL_BYTES.get(dom)
     roofline = None
@@ -158,7 +174,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32 quantiser, i32/bit codec", "data": "synthetic",
         "config": {"workload": wl.name, "tensors": len(xs), "numel": total, "eb": eb, "radius": 512,
-                   "chunk": 4096, "sub": args.sub, "p_zero": wl.p_zero, "box_k": wl.k,
+                   "chunk": 4096, "sub": args.sub, "streams": S, "p_zero": wl.p_zero, "box_k": wl.k,
                    "seed_base": wl.seed(0)},
         "compression_ratio": round(4.0 * total / comp_bytes, 4),
         "compressed_bytes_held": comp_bytes,

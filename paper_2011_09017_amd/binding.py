@@ -157,7 +157,8 @@ class Context:
             self._h = None
 
     def __del__(self):
-        self.close()
+        if cmp_destroy is not None:                  # module globals are gone at interpreter exit
+            self.close()
 
     def _stream(self) -> int:
         return torch.cuda.current_stream(self.device).cuda_stream
@@ -188,15 +189,15 @@ class Context:
             raise CmpError(rc, "cmp_decompress")
         return out
 
-    def last_status(self) -> int:
-        return cmp_last_status(self._h, self._stream())
+    def last_status(self, stream: int | None = None) -> int:
+        return cmp_last_status(self._h, self._stream() if stream is None else stream)
 
     def profile(self, enable: bool) -> None:
         cmp_profile(self._h, enable)
 
-    def profile_read(self) -> dict:
+    def profile_read(self, stream: int | None = None) -> dict:
         """{kernel name: (total ms, launches)} since profile(True)."""
-        n, d = cmp_profile_read(self._h, self._stream())
+        n, d = cmp_profile_read(self._h, self._stream() if stream is None else stream)
         if n < 0:
             raise CmpError(n, "cmp_profile_read")
         return d

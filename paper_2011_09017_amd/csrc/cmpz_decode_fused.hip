@@ -2,28 +2,40 @@
 // (row and column prefix sums) -> de-quantisation, one pass, residuals never
 // leave the CU.  HBM traffic is the container read plus the 4-byte result write.
 //
-// A workgroup owns whole planes.  Planes no larger than the band capacity are
-// processed several at a time; a larger plane is walked in bands of whole rows
-// with one running column sum per thread (needs W <= 256).  Shapes that fit
-// neither case take the unfused kernels of cmpz_decompress.hip.
+// The unit of work is a band: whole rows of one plane, or several whole small
+// planes, at most 2048 elements.  Every WAVE owns its bands and its own slice
+// of LDS and walks through them on its own: after the decode tables are built
+// there is no workgroup barrier, so while one wave of a CU decodes (LDS and
+// ALU latency), another runs its column pass (stores) and a third waits for
+// its next payload.  The four waves of a workgroup share only the tables.
+// Planes larger than a band are walked band by band with running column sums
+// (needs W <= 256).  Shapes that fit neither case take the unfused kernels of
+// cmpz_decompress.hip.
 //
 // A band is decoded by one lane per sub-block (the container stores each
 // sub-block's bit count, so every lane knows where its codes start) into an LDS
-// array of int32.  In a band without outliers a lane adds up its residuals along
-// the row while it decodes them, so what it stores is already the row prefix sum
-// up to a per-lane carry; a short segmented scan over the lanes' totals yields the
-// carries and the column pass adds them on the fly.  A band with outliers stores
-// plain residuals, patches the outliers in and runs an explicit row scan.
-// The bit counts and offsets of the next band are fetched while the current one
-// is processed.
+// array of int32.  The band's stretch of the payload is contiguous in the
+// container; it is copied into LDS with 128-bit loads first, and the lanes read
+// their codewords from there at arbitrary bit positions (a band whose payload
+// exceeds the staging buffer, more than 8 bits per code on average, is decoded
+// straight from memory instead).  In a band without outliers a lane adds up its
+// residuals along the row while it decodes them, so what it stores is already the
+// row prefix sum up to a per-lane carry; one segmented scan over the lanes'
+// totals yields the carries, and the column pass adds them on the fly.  A band
+// with outliers stores plain residuals, patches the outliers in and runs an
+// explicit row scan.
+// Software pipeline: the bit counts of the next band are fetched during the
+// decode of the current one, and its payload during the column pass.
 #include "cmpz_decode_core.h"
 
 namespace cmpz {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves   = kThreads / kWave;
-constexpr int kBandMax = 8192;                    // elements decoded per band at most
+constexpr int kThreads    = 256;
+constexpr int kWaves      = kThreads / kWave;
+constexpr int kBandMax    = 2048;                 // elements decoded per band at most
+constexpr int kStageWords = 512;                  // staged payload per band: 2 KB, i.e. 8 bits per code of a full band
+constexpr int kColGroups  = 4;                    // 64-column groups of a big plane (W <= 256)
 
 template <int SUB> struct Cfg;
 template <> struct Cfg<128> { static constexpr int kLog = 7; };
@@ -44,32 +56,40 @@ struct FusedPlan {
 #define PHASE(k)
 #endif
 
+// LDS written by some lanes of a wave is read by others: the hardware keeps a wave's LDS
+// operations in order, this keeps the compiler from moving them across.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 struct Band {
     uint32_t e0, n, rows, plane0, npl, row0;
     bool valid;
 };
 
-// What a thread fetches ahead for a band: its two bit-count entries, its lane's chunk bounds,
-// and (uniform) the band's range in the outlier list.
-struct Ahead {
-    uint32_t v0, v1, uu0, uu1, olo, ohi;
+// The stretch of the payload a band's lanes read.
+struct Stage {
+    uint32_t q0;           // first 16-byte unit staged
+    uint32_t nq;           // units staged; 0 = not staged (the band decodes from memory)
 };
 
 template <int SUB>
-__global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, FusedPlan pl)
+__global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, FusedPlan pl)
 {
     constexpr int kLog  = Cfg<SUB>::kLog;
-    constexpr int kNDec = kBandMax / SUB;                 // decode lanes per band
+    constexpr int kND   = kBandMax / SUB;                 // decode lanes per band
     constexpr int kNSub = (int)kChunk / SUB;              // sub-blocks per chunk
-    constexpr int kPre  = kNSub + kNDec;                  // bit-count entries looked at per band
+    constexpr int kPre  = kNSub + kND;                    // bit-count entries looked at per band
+    constexpr int kE    = (kPre + kWave - 1) / kWave;     // of which each lane fetches kE consecutive ones
+    static_assert(2 * kND <= kStageWords, "the lane records live in the staging buffer");
+    static_assert(kStageWords / 4 == 2 * kWave, "two units per lane");
 
-    __shared__ int32_t  R[kBandMax + kNDec];              // one pad word per sub-block: lane-conflict free
     __shared__ DecodeTables T;
-    __shared__ uint32_t P[kPre + 1];                      // exclusive prefix of sub-block bit counts
-    __shared__ uint32_t wave_tot[kWaves];
-    __shared__ int32_t  lane_tail[kNDec];                 // row-sum at the end of each decode lane's run
-    __shared__ uint32_t lane_reset[kNDec];                // offset of the lane's first row start (SUB = none)
-    __shared__ int32_t  lane_carry[kNDec];                // what the lane's elements before that offset lack
+    __shared__ int32_t  Rs[kWaves][kBandMax + kND];       // one pad word per sub-block: lane-conflict free
+    __shared__ uint32_t Ps[kWaves][kE * kWave + 2];       // exclusive prefix of sub-block bit counts
+    __shared__ __align__(16) uint32_t Ss[kWaves][kStageWords + 4];   // staged payload; after the decode, the lane records
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
 #ifdef CMPZ_PHASE_CLOCKS
@@ -78,13 +98,20 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, Fus
 #endif
     // every workgroup validates the container and builds the decode tables for itself
     {
-        const uint32_t defect = build_tables_256(T, a, reinterpret_cast<uint32_t *>(R));
+        const uint32_t defect = build_tables_256(T, a, reinterpret_cast<uint32_t *>(&Rs[0][0]));
         if (defect) {
             if (blockIdx.x == 0 && tid == 0) atomicOr(a.status, defect);
             return;
         }
     }
     PHASE(0)
+    // ---- from here on the waves are on their own ----
+    int32_t  *R = Rs[wv];
+    uint32_t *P = Ps[wv];
+    uint32_t *S = Ss[wv];
+    // per decode lane, after the decode: .x = offset of the lane's first row start (elements before
+    // it lack the carry), .y = the carry
+    uint2 *RC = reinterpret_cast<uint2 *>(S);
     const uint32_t payload_units = T.payload_units, n_outl = T.n_outliers;
 
     const uint32_t W = a.W, H = a.H, HW = a.HW, R0 = a.radius;
@@ -94,8 +121,15 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, Fus
     const Header *hd = reinterpret_cast<const Header *>(a.buf);
     const uint32_t *__restrict__ oidx = reinterpret_cast<const uint32_t *>(a.buf + hd->off_outl_idx);
     const int32_t *__restrict__ oval = reinterpret_cast<const int32_t *>(a.buf + hd->off_outl_val);
+    const uint4 *__restrict__ payload4 = reinterpret_cast<const uint4 *>(a.buf + a.lay.off_payload);
     const float s = a.s;
     bool bad = false;
+
+    // What a lane fetches ahead for a band: its bit-count entries, its sub-block's chunk bounds,
+    // and (uniform) the band's range in the outlier list and the payload bounds of its chunks.
+    struct Ahead {
+        uint32_t v[kE], uu0, uu1, olo, ohi, cf, cl, cl1;
+    };
 
     auto band_of = [&](uint32_t item, uint32_t b) -> Band {
         Band g;
@@ -114,55 +148,111 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, Fus
         return g;
     };
     auto fetch = [&](const Band &g) -> Ahead {
-        Ahead f = {0, 0, 0, 0, 0, 0};
+        Ahead f;
+#pragma unroll
+        for (int i = 0; i < kE; ++i) f.v[i] = 0;
+        f.uu0 = f.uu1 = f.olo = f.ohi = f.cf = f.cl = f.cl1 = 0;
         if (!g.valid) return f;
         const uint32_t sb0 = g.e0 >> kLog, sb1 = (g.e0 + g.n - 1) >> kLog;
         const uint32_t j0 = sb0 & (kNSub - 1), ent0 = sb0 - j0, nent = j0 + (sb1 - sb0 + 1);
-        if (2u * tid < nent) f.v0 = sub_bits[(uint64_t)ent0 + 2u * tid];
-        if (2u * tid + 1 < nent) f.v1 = sub_bits[(uint64_t)ent0 + 2u * tid + 1];
-        if (sb0 + tid <= sb1) {
-            const uint32_t c = (sb0 + tid) / kNSub;
+#pragma unroll
+        for (int i = 0; i < kE; ++i) {
+            const uint32_t e = (uint32_t)kE * lane + i;
+            if (e < nent) f.v[i] = sub_bits[(uint64_t)ent0 + e];
+        }
+        if (sb0 + lane <= sb1) {
+            const uint32_t c = (sb0 + lane) / kNSub;
             f.uu0 = chunk_off[c]; f.uu1 = chunk_off[c + 1];
         }
         f.olo = outl_off[g.e0 / kChunk];
         f.ohi = outl_off[(g.e0 + g.n - 1) / kChunk + 1];
+        f.cf = chunk_off[sb0 / kNSub];
+        f.cl = chunk_off[sb1 / kNSub];
+        f.cl1 = chunk_off[sb1 / kNSub + 1];
         return f;
+    };
+    // exclusive prefix of a band's bit counts from the start of its first chunk
+    auto prefix_bits = [&](const Ahead &f) {
+        uint32_t loc = 0;
+#pragma unroll
+        for (int i = 0; i < kE; ++i) loc += f.v[i];
+        const uint32_t inc = wave_inclusive_sum(loc);
+        uint32_t ex = inc - loc;
+#pragma unroll
+        for (int i = 0; i < kE; ++i) { P[kE * lane + i] = ex; ex += f.v[i]; }
+        if (lane == 63) P[kE * kWave] = inc;
+        wave_sync();
+    };
+    // the band's stretch of the payload (uniform; needs P): from the word where its first
+    // sub-block starts, rounded down to a unit, to the word where its last sub-block ends
+    auto stage_of = [&](const Band &g, const Ahead &f) -> Stage {
+        Stage st = {0, 0};
+        if (!g.valid) return st;
+        const uint32_t sb0 = g.e0 >> kLog, sb1 = (g.e0 + g.n - 1) >> kLog;
+        const uint32_t j0 = sb0 & (kNSub - 1), jl = sb1 & (kNSub - 1), idxl = j0 + (sb1 - sb0);
+        const uint32_t first_bit = P[j0] - P[0];                 // in the first chunk's stream
+        const uint32_t end_bit = P[idxl + 1] - P[idxl - jl];     // in the last chunk's stream
+        if (!(f.cf <= f.cl && f.cl <= f.cl1 && f.cl1 <= payload_units)) return st;
+        const uint64_t w_lo = (uint64_t)f.cf * 4 + (first_bit >> 5);
+        const uint64_t w_hi = (uint64_t)f.cl * 4 + ((uint64_t)end_bit + 31) / 32;
+        if (w_hi > (uint64_t)f.cl1 * 4 || w_hi <= w_lo) return st;
+        const uint64_t q0 = w_lo >> 2, q1 = (w_hi + 3) >> 2;
+        if (q1 - q0 > (uint64_t)(kStageWords / 4)) return st;
+        st.q0 = (uint32_t)q0; st.nq = (uint32_t)(q1 - q0);
+        return st;
+    };
+    auto stage_load = [&](const Stage &st, uint4 &s0, uint4 &s1) {
+        if ((uint32_t)lane < st.nq) s0 = payload4[(uint64_t)st.q0 + lane];
+        if ((uint32_t)lane + kWave < st.nq) s1 = payload4[(uint64_t)st.q0 + lane + kWave];
     };
 
     const uint32_t nbands_big = pl.big ? (H + pl.Rb - 1) / pl.Rb : 1u;
-    uint32_t item = blockIdx.x, b = 0;
+    const uint32_t item_stride = gridDim.x * kWaves;
+    uint32_t item = blockIdx.x * kWaves + wv, b = 0;
     Band cur = band_of(item, b);
     Ahead fa = fetch(cur);
-    int32_t colacc = 0;                                      // running column sum (big planes)
+    int32_t colacc[kColGroups] = {0, 0, 0, 0};               // running column sums (big planes)
+    uint4 s0 = make_uint4(0, 0, 0, 0), s1 = s0;
+    Stage sg = {0, 0};
+    if (cur.valid) {
+        prefix_bits(fa);
+        sg = stage_of(cur, fa);
+        stage_load(sg, s0, s1);
+    }
 
     while (cur.valid) {
-        // ---- next band: geometry now, loads in flight while this band is processed ----
+        // ---- next band: geometry now, bit counts in flight while this band is decoded ----
         uint32_t nitem = item, nb = b + 1;
-        if (nb >= nbands_big) { nitem = item + gridDim.x; nb = 0; }
+        if (nb >= nbands_big) { nitem = item + item_stride; nb = 0; }
         const Band nxt = band_of(nitem, nb);
         const Ahead fn = fetch(nxt);
 
         const uint32_t e0 = cur.e0, n = cur.n, rows = cur.rows, npl = cur.npl;
         const uint32_t sb0 = e0 >> kLog;
         const uint32_t sb1 = (e0 + n - 1) >> kLog;
-        const uint32_t nsb = sb1 - sb0 + 1;              // <= kNDec by construction of the plan
+        const uint32_t nsb = sb1 - sb0 + 1;              // <= kND by construction of the plan
         const uint32_t base = sb0 << kLog;
         const uint32_t u0 = e0 - base;
         const uint32_t j0 = sb0 & (kNSub - 1);           // position of sb0 in its chunk
-        if (b == 0) colacc = 0;
-
-        // ---- exclusive prefix of the bit counts from the start of the first chunk ----
-        {
-            const uint32_t inc = wave_inclusive_sum(fa.v0 + fa.v1);
-            if (lane == 63) wave_tot[wv] = inc;
-            __syncthreads();
-            uint32_t wbase = 0;
-            for (int k = 0; k < wv; ++k) wbase += wave_tot[k];
-            const uint32_t ex = wbase + inc - (fa.v0 + fa.v1);
-            if (2 * tid < kPre + 1) P[2 * tid] = ex;
-            if (2 * tid + 1 < kPre + 1) P[2 * tid + 1] = ex + fa.v0;
-            __syncthreads();
+        if (b == 0) {
+#pragma unroll
+            for (int c = 0; c < kColGroups; ++c) colacc[c] = 0;
         }
+
+        // this lane's sub-block in its chunk's stream (P is rewritten for the next band below)
+        uint32_t start = 0, sbits = 0;
+        if (lane < (int)nsb) {
+            const uint32_t j = (sb0 + lane) & (kNSub - 1);
+            const uint32_t idx = j0 + lane;
+            start = P[idx] - P[idx - j];
+            sbits = P[idx + 1] - P[idx];
+        }
+        const bool staged = sg.nq != 0;                  // uniform
+        if (staged) {
+            if ((uint32_t)lane < sg.nq) reinterpret_cast<uint4 *>(S)[lane] = s0;
+            if ((uint32_t)lane + kWave < sg.nq) reinterpret_cast<uint4 *>(S)[lane + kWave] = s1;
+        }
+        wave_sync();
         PHASE(1)
 
         // outliers of the band: a range of the outlier list (filtered by index below)
@@ -171,12 +261,10 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, Fus
         const bool folded = (olo == ohi);                // uniform: no outliers, rows are summed while decoding
 
         // ---- decode: one lane per sub-block ----
-        if (tid < (int)nsb) {
-            const uint32_t g = sb0 + tid;
-            const uint32_t j = g & (kNSub - 1);
-            const uint32_t idx = j0 + tid;
-            const uint32_t start = P[idx] - P[idx - j];
-            const uint32_t sbits = P[idx + 1] - P[idx];
+        int32_t my_tail = 0;
+        uint32_t my_reset = 0;
+        if (lane < (int)nsb) {
+            const uint32_t g = sb0 + lane;
             const uint32_t uu0 = fa.uu0, uu1 = fa.uu1;
             bool lbad = !(uu0 <= uu1 && uu1 <= payload_units);
             const uint32_t nw = lbad ? 0u : (uu1 - uu0) * 4;
@@ -186,114 +274,97 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, Fus
             // elements of this sub-block that belong to the band: k in [klo, khi)
             const uint32_t klo = (el0 < e0) ? e0 - el0 : 0u;
             const uint32_t khi = (el0 + n_here > e0 + n) ? e0 + n - el0 : n_here;
-            int32_t *my = R + tid * (SUB + 1);
+            int32_t *my = R + lane * (SUB + 1);
+            my_reset = klo;
+            // position of the sub-block in the staging buffer (its chunk must lie in the staged stretch)
+            uint32_t spos = 0;
+            if (staged && !lbad) {
+                const int64_t rel = ((int64_t)uu0 - (int64_t)sg.q0) * 128 + (int64_t)start;
+                if (rel < 0 || rel + (int64_t)sbits > (int64_t)sg.nq * 128) lbad = true;
+                else spos = (uint32_t)rel;
+            }
             uint32_t end = 0;
             if (!lbad) {
+                // row starts among the lane's elements from klo on (the band begins at one)
+                uint32_t w_first = 0;
+                if (folded) {
+                    const uint32_t l_first = el0 + klo - e0;             // band-local index of the first element
+                    w_first = l_first - pl.divW.div(l_first) * W;
+                }
                 const uint32_t last = nw - 1;
                 const uint32_t *__restrict__ gw =
                     reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_payload + (uint64_t)uu0 * 16);
-                auto rd = [&](uint32_t k) -> uint32_t { return gw[k < last ? k : last]; };
-                // runs of 32 codewords are decoded from a register queue, longer ones straight from memory
-                auto run_decode = [&](auto put) -> uint32_t {
-                    if constexpr (SUB == 32) return decode_run_regs(T, gw, last, start, khi, klo, R0, put, lbad);
-                    else return decode_run<false>(T, rd, start, khi, klo, R0, put, lbad);
+                auto run_decode = [&](uint32_t count, uint32_t skip, auto put) -> uint32_t {
+                    if (staged)
+                        return decode_lds(T, S, sg.nq * 4 - 1, spos, count, skip, R0, put, lbad) - spos + start;
+                    return decode_run<false>(T, [&](uint32_t k) -> uint32_t { return gw[k < last ? k : last]; }, start,
+                                             count, skip, R0, put, lbad);
                 };
-                if (SUB == 32 && n_here == 32u) {
-                    // complete 32-codeword sub-block: unrolled decoder, all 32 slots of the lane are
-                    // written (those outside the band are never read)
-                    uint32_t mask = 0, first_reset = (uint32_t)SUB;
-                    if (folded) {
-                        // row starts among the lane's elements from klo on (the band begins at one)
-                        const uint32_t l_first = el0 + klo - e0;
-                        const uint32_t w_first = l_first - pl.divW.div(l_first) * W;
-                        uint32_t k0 = klo + (w_first ? W - w_first : 0u);
-                        first_reset = k0 < 32u ? k0 : (uint32_t)SUB;
-                        for (; k0 < 32u; k0 += W) mask |= 1u << k0;
-                        end = decode32<true>(T, gw, last, start, mask, (int32_t)R0, my, lbad);
-                        lane_tail[tid] = my[khi - 1];
-                        lane_reset[tid] = first_reset;
-                    } else {
-                        end = decode32<false>(T, gw, last, start, 0u, (int32_t)R0, my, lbad);
-                    }
+                if (SUB == 32 && n_here == 32u && folded) {
+                    // complete 32-codeword sub-block: the row starts as a bit mask; all 32 slots of
+                    // the lane are written (those outside the band are never read)
+                    uint32_t mask = 0;
+                    uint32_t k0 = klo + (w_first ? W - w_first : 0u);
+                    my_reset = k0 < 32u ? k0 : (uint32_t)SUB;
+                    for (; k0 < 32u; k0 += W) mask |= 1u << k0;
+                    int32_t run = 0;
+                    end = run_decode(32u, 0u, [&](uint32_t k, uint32_t sy) {
+                        const int32_t keep = ~__builtin_amdgcn_sbfe((int)mask, k, 1);     // 0 where the row restarts
+                        run = (run & keep) + ((int32_t)sy - (int32_t)R0);
+                        my[k] = run;
+                    });
+                    my_tail = my[khi - 1];
                 } else if (folded) {
                     // running sum along the row, restarted at every row start
-                    const uint32_t l_first = el0 + klo - e0;             // band-local index of the first element
-                    uint32_t w = l_first - pl.divW.div(l_first) * W;
+                    uint32_t w = w_first;
                     int32_t run = 0;
                     uint32_t first_reset = (uint32_t)SUB;
-                    end = run_decode([&](uint32_t k, uint32_t sy) {
+                    end = run_decode(khi, klo, [&](uint32_t k, uint32_t sy) {
                         const int32_t d = (int32_t)sy - (int32_t)R0;
                         if (w == 0) { run = 0; first_reset = first_reset < k ? first_reset : k; }
                         run += d;
                         my[k] = run;
                         w = (w + 1 == W) ? 0u : w + 1;
                     });
-                    lane_tail[tid] = run;
-                    lane_reset[tid] = first_reset;
+                    my_tail = run;
+                    my_reset = first_reset;
                 } else {
-                    end = run_decode([&](uint32_t k, uint32_t sy) { my[k] = (int32_t)sy - (int32_t)R0; });
+                    const bool whole = (SUB == 32 && n_here == 32u);
+                    end = run_decode(whole ? 32u : khi, whole ? 0u : klo,
+                                     [&](uint32_t k, uint32_t sy) { my[k] = (int32_t)sy - (int32_t)R0; });
                 }
-            } else {
-                lane_tail[tid] = 0; lane_reset[tid] = klo;
             }
             // a sub-block decoded to its end must land exactly on its stored bit count
-            if ((khi == n_here || (SUB == 32 && n_here == 32u)) && end != start + sbits) lbad = true;
+            if (!lbad && (khi == n_here || (SUB == 32 && n_here == 32u)) && end != start + sbits) lbad = true;
             bad |= lbad;
-#ifdef CMPZ_PHASE_CLOCKS
-            if (tid == 0) { const long long now_ = clock64(); clk[6] += now_ - last_; last_ = now_; }
-#endif
         }
-        __syncthreads();
+        wave_sync();                                     // S is free: the lane records take its place
         PHASE(3)
 
         if (folded) {
             // ---- carries: what each lane's leading elements (before its first row start) lack ----
-            if (wv == 0) {
-                int32_t chain = 0;                                   // row-sum flowing out of the previous 64 lanes
-                for (uint32_t t0 = 0; t0 < nsb; t0 += 64) {
-                    const uint32_t t = t0 + lane;
-                    const bool in = t < nsb;
-                    int32_t v = in ? lane_tail[t] : 0;
-                    uint32_t f = (in && lane_reset[t] != (uint32_t)SUB) ? 1u : 0u;   // the lane's run contains a row start
-                    wave_segmented_sum(v, f);                        // v: row-sum at the end of lane t, within this group
-                    if (!f) v += chain;
-                    // exclusive: what flows into lane t is the inclusive value of lane t-1
-                    int32_t into = (int32_t)dpp_u32<0x138, 0xf>((uint32_t)v);        // wave_shr:1
-                    if (lane == 0) into = chain;
-                    if (in) lane_carry[t] = into;
-                    chain = __builtin_amdgcn_readlane(v, 63);
-                }
-            }
-            __syncthreads();
-            // every decode lane adds its carry to the elements before its first row start
-            if (tid < (int)nsb) {
-                const int32_t cy = lane_carry[tid];
-                const uint32_t el0 = (sb0 + tid) << kLog;
-                const uint32_t n_here = (a.numel - el0 >= (uint32_t)SUB) ? (uint32_t)SUB : a.numel - el0;
-                const uint32_t klo = (el0 < e0) ? e0 - el0 : 0u;
-                uint32_t khi = (el0 + n_here > e0 + n) ? e0 + n - el0 : n_here;
-                const uint32_t fr = lane_reset[tid];
-                khi = khi < fr ? khi : fr;
-                int32_t *my = R + tid * (SUB + 1);
-                if (cy != 0) for (uint32_t k = klo; k < khi; ++k) my[k] += cy;
-            }
+            int32_t v = my_tail;                                        // 0 in lanes without a sub-block
+            uint32_t f = (lane < (int)nsb && my_reset != (uint32_t)SUB) ? 1u : 0u;   // the lane's run contains a row start
+            wave_segmented_sum(v, f);                                   // v: row-sum at the end of the lane's run
+            // what flows into a lane is the inclusive value of the lane before it; a band begins a row
+            int32_t into = (int32_t)dpp_u32<0x138, 0xf>((uint32_t)v);   // wave_shr:1
+            if (lane == 0) into = 0;
+            if (lane < kND) RC[lane] = make_uint2(lane < (int)nsb ? my_reset : 0u, (uint32_t)into);
         } else {
+            if (lane < kND) RC[lane] = make_uint2(0u, 0u);
             // ---- outliers overwrite their residuals, then an explicit row scan ----
-            for (uint32_t k = olo + tid; k < ohi; k += kThreads) {
+            for (uint32_t k = olo + lane; k < ohi; k += kWave) {
                 const uint32_t i = oidx[k];
                 if (i >= e0 && i - e0 < n) {
                     const uint32_t u = i - base;
                     R[u + (u >> kLog)] = oval[k];
                 }
             }
-            __syncthreads();
-            const uint32_t r_lo = (uint32_t)(((uint64_t)rows * wv) / kWaves);
-            const uint32_t r_hi = (uint32_t)(((uint64_t)rows * (wv + 1)) / kWaves);
-            const uint32_t l_lo = r_lo * W, l_hi = r_hi * W;
+            wave_sync();
             int32_t carry = 0;
-            for (uint32_t l0 = l_lo; l0 < l_hi; l0 += 64) {
+            for (uint32_t l0 = 0; l0 < n; l0 += kWave) {
                 const uint32_t l = l0 + lane;
-                const bool in = l < l_hi;
+                const bool in = l < n;
                 const uint32_t u = l + u0;
                 const uint32_t ph = u + (u >> kLog);
                 int32_t v = in ? R[ph] : 0;
@@ -304,47 +375,68 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, Fus
                 carry = __builtin_amdgcn_readlane(v, 63);
             }
         }
-        __syncthreads();
+        wave_sync();
         PHASE(4)
 
-        // ---- column prefix sums; wide rows are de-quantised and stored from here ----
+        // ---- next band: bit positions now, its payload in flight during the column pass ----
+        Stage sgn = {0, 0};
+        if (nxt.valid) {                                 // uniform
+            prefix_bits(fn);
+            sgn = stage_of(nxt, fn);
+            stage_load(sgn, s0, s1);
+        }
+        PHASE(2)
+
+        // ---- column prefix sums (adding the lanes' carries); wide rows are de-quantised and stored from here ----
         const bool direct = W >= 32;                     // a wave then stores runs of >= 128 bytes
-        {
-            const uint32_t ncols = pl.big ? W : npl * W;
-            const uint32_t nrow = pl.big ? rows : H;
-            for (uint32_t col = tid; col < ncols; col += kThreads) {
-                const uint32_t p = pl.big ? 0u : pl.divW.div(col);
-                const uint32_t w = col - p * W;
-                int32_t acc = pl.big ? colacc : 0;
-                uint32_t u = p * HW + w + u0;
-                float *__restrict__ dst = a.xout + e0 + p * HW + w;
-                uint32_t h = 0;
-                for (; h + 8 <= nrow; h += 8) {          // 8 rows at a time: loads in flight together
-                    int32_t t8[8];
-                    uint32_t ph[8];
+        const uint32_t nrow = pl.big ? rows : H;
+        auto walk = [&](uint32_t col, int32_t acc) -> int32_t {
+            const uint32_t p = pl.big ? 0u : pl.divW.div(col);
+            const uint32_t w = col - p * W;
+            uint32_t u = p * HW + w + u0;
+            float *__restrict__ dst = a.xout + e0 + p * HW + w;
+            uint32_t h = 0;
+            for (; h + 8 <= nrow; h += 8) {              // 8 rows at a time: loads in flight together
+                int32_t t8[8];
+                uint32_t ph[8], kk[8];
+                uint2 rc[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) { const uint32_t uq = u + q * W; ph[q] = uq + (uq >> kLog); t8[q] = R[ph[q]]; }
+                for (int q = 0; q < 8; ++q) {
+                    const uint32_t uq = u + q * W, t = uq >> kLog;
+                    ph[q] = uq + t; kk[q] = uq & (uint32_t)(SUB - 1);
+                    t8[q] = R[ph[q]]; rc[q] = RC[t];
+                }
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        acc += t8[q];
-                        if (direct) dst[(h + q) * W] = (float)acc * s; else R[ph[q]] = acc;
-                    }
-                    u += 8 * W;
+                for (int q = 0; q < 8; ++q) {
+                    acc += t8[q] + ((kk[q] < rc[q].x) ? (int32_t)rc[q].y : 0);
+                    if (direct) dst[(h + q) * W] = (float)acc * s; else R[ph[q]] = acc;
                 }
-                for (; h < nrow; ++h, u += W) {
-                    const uint32_t ph = u + (u >> kLog);
-                    acc += R[ph];
-                    if (direct) dst[h * W] = (float)acc * s; else R[ph] = acc;
-                }
-                if (pl.big) colacc = acc;
+                u += 8 * W;
             }
+            for (; h < nrow; ++h, u += W) {
+                const uint32_t t = u >> kLog, ph = u + t;
+                const uint2 rc = RC[t];
+                acc += R[ph] + (((u & (uint32_t)(SUB - 1)) < rc.x) ? (int32_t)rc.y : 0);
+                if (direct) dst[h * W] = (float)acc * s; else R[ph] = acc;
+            }
+            return acc;
+        };
+        if (pl.big) {
+#pragma unroll
+            for (int c = 0; c < kColGroups; ++c) {
+                const uint32_t col = c * kWave + lane;
+                if (col < W) colacc[c] = walk(col, colacc[c]);
+            }
+        } else {
+            const uint32_t ncols = npl * W;
+            for (uint32_t col = lane; col < ncols; col += kWave) (void)walk(col, 0);
         }
 
         // ---- narrow rows: de-quantise and store from LDS, 128 bits at a time ----
         if (!direct) {
-            __syncthreads();
+            wave_sync();
             const uint32_t q_lo = e0 >> 2, q_hi = (e0 + n + 3) >> 2;       // global quads touched
-            for (uint32_t qd = q_lo + tid; qd < q_hi; qd += kThreads) {
+            for (uint32_t qd = q_lo + lane; qd < q_hi; qd += kWave) {
                 const uint32_t i = qd << 2;
                 float o[4];
                 bool ok[4];
@@ -363,9 +455,9 @@ __global__ __launch_bounds__(kThreads) void k_decode_fused(DecompressArgs a, Fus
                 }
             }
         }
-        __syncthreads();                                  // R and the lane arrays are reused by the next band
+        wave_sync();                                      // R and the staging buffer are reused by the next band
         PHASE(5)
-        cur = nxt; fa = fn; item = nitem; b = nb;
+        cur = nxt; fa = fn; sg = sgn; item = nitem; b = nb;
     }
     if (bad) atomicOr(a.status, kStFormat);
 #ifdef CMPZ_PHASE_CLOCKS
@@ -387,13 +479,15 @@ bool launch_decode_fused(const DecompressArgs &a, Profiler *prof, hipStream_t st
     if (a.HW <= cap) {
         pl.big = 0; pl.G = (uint32_t)(cap / a.HW); pl.Rb = 0;
         pl.nitems = (a.planes + pl.G - 1) / pl.G;
-    } else if (a.W <= (uint32_t)kThreads) {
+    } else if (a.W <= (uint32_t)(kColGroups * kWave) && a.W <= cap) {
         pl.big = 1; pl.G = 1; pl.Rb = (uint32_t)(cap / a.W);
         pl.nitems = a.planes;
     } else {
         return false;
     }
-    const uint32_t grid = pl.nitems < 256u * 8u ? pl.nitems : 256u * 8u;
+    // every workgroup builds the decode tables once and then loops: no more workgroups than fit the chip
+    const uint32_t want = (pl.nitems + kWaves - 1) / kWaves;
+    const uint32_t grid = want < 256u * 3u ? want : 256u * 3u;
     switch (a.sub) {
     case 32:  launch(prof, kKDecodeFused, k_decode_fused<32>, dim3(grid), dim3(kThreads), st, a, pl); break;
     case 64:  launch(prof, kKDecodeFused, k_decode_fused<64>, dim3(grid), dim3(kThreads), st, a, pl); break;

@@ -140,8 +140,8 @@ __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, Decode
         T.t1[idx] = (uint16_t)e;
     }
     // level 2: entry i covers left-aligned values t32 + [i << sh, (i+1) << sh)
-    {
-        const uint32_t idx = tid;                            // kT2Size == 1024 threads
+    if ((uint32_t)tid < kT2Size) {
+        const uint32_t idx = tid;
         uint32_t e = 0;
         const uint64_t v = (uint64_t)T.t32 + ((uint64_t)idx << T.sh);
         if (T.has_long && v < (1ull << 32)) {
