@@ -21,7 +21,8 @@ constexpr uint32_t kT2Size = 1u << kT2Bits;
 struct DecodeTables {
     uint16_t t1[kT1Size];
     uint16_t t2[kT2Size];
-    uint16_t sorted[kMaxSym];     // symbols ordered by (length, symbol)
+    uint16_t sorted[kMaxSym];     // symbols ordered by (length, symbol), each as its residual
+                                  // (symbol - radius) in 10 bits, two's complement
     uint64_t first[64];           // first canonical code of each length
     uint32_t count[64];           // codes of each length
     uint32_t offs[64];            // index into sorted[] of the first symbol of each length
@@ -196,7 +197,7 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
     // symbols ordered by (length, symbol)
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-        if (L[q]) T.sorted[T.offs[L[q]] + wave_cnt[q * 4 + wv][L[q]] + in_wave[q]] = (uint16_t)(q * 256 + tid);
+        if (L[q]) T.sorted[T.offs[L[q]] + wave_cnt[q * 4 + wv][L[q]] + in_wave[q]] = (uint16_t)((q * 256 + tid - a.radius) & 1023u);
     __syncthreads();
 
     // level 1: entry idx is the codeword (if any, of at most kLB bits) that prefixes idx
@@ -245,18 +246,24 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
     return 0;
 }
 
+// Table entries are length << 10 | residual, the residual (symbol - radius) in 10 bits.
+__device__ __forceinline__ int32_t entry_residual(uint32_t e)
+{
+    return __builtin_amdgcn_sbfe((int)e, 0, 10);
+}
+
 // Decode `count` codewords that start at bit `start` of a chunk stream whose 32-bit words
 // are read through rd(word index); rd must be safe for any index (clamp) -- words past the
 // stream only ever reach bits that a well-formed stream does not consume.  put(k, symbol) is
-// called for k >= klo.  Returns the bit position after the last codeword; sets bad when a
+// called for k >= klo, where the second argument is the residual symbol - radius (the outlier
+// marker, symbol 0, arrives as -radius).  Returns the bit position after the last codeword; sets bad when a
 // bit pattern matches no codeword.
 //
 // The bit window is refilled from a word fetched one refill ahead, so the only memory
 // latency on the per-symbol dependency chain is the table lookup.
 template <bool EAGER, class RD, class PUT>
 __device__ __forceinline__ uint32_t decode_run(const DecodeTables &T, RD rd, uint32_t start, uint32_t count,
-                                               uint32_t klo, uint32_t fallback_sym, PUT put, bool &bad,
-                                               long long *dbg_t0 = nullptr)
+                                               uint32_t klo, PUT put, bool &bad)
 {
     uint32_t wi = start >> 5;
     uint64_t win = ((((uint64_t)rd(wi)) << 32) | rd(wi + 1)) << (start & 31);
@@ -264,9 +271,6 @@ __device__ __forceinline__ uint32_t decode_run(const DecodeTables &T, RD rd, uin
     wi += 2;
     uint32_t nxt = rd(wi);
     const uint32_t t32 = T.t32, sh = T.sh, has_long = T.has_long;
-#ifdef CMPZ_PHASE_CLOCKS
-    if (dbg_t0) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); *dbg_t0 = clock64(); }
-#endif
     for (uint32_t k = 0; k < count; ++k) {
         if (EAGER) {
             // cheap reads (LDS): branch-free refill, the next word is refetched every step
@@ -298,7 +302,7 @@ __device__ __forceinline__ uint32_t decode_run(const DecodeTables &T, RD rd, uin
                 const uint32_t w0 = pos >> 5, off = pos & 31;
                 uint64_t w64 = ((((uint64_t)rd(w0)) << 32) | rd(w0 + 1)) << off;
                 if (off) w64 |= (uint64_t)(rd(w0 + 2) >> (32 - off));
-                uint32_t len = 0, sy = fallback_sym;
+                uint32_t len = 0, sy = 0;                    // no match: residual 0
                 for (uint32_t L = kLB + 1; L <= T.max_len; ++L) {
                     const uint64_t code = w64 >> (64 - L);
                     if (code >= T.first[L] && code - T.first[L] < T.count[L]) {
@@ -319,34 +323,36 @@ __device__ __forceinline__ uint32_t decode_run(const DecodeTables &T, RD rd, uin
         }
         const uint32_t len = e >> 10;
         if (len < 64u) { win <<= len; avail -= (int)len; }
-        if (k >= klo) put(k, e & 1023u);
+        if (k >= klo) put(k, entry_residual(e));
     }
     return 32u * wi - (uint32_t)avail;
 }
 
-// Decoder for a bit stream staged in LDS.  S[0 .. wmax + 2] are readable words; bit p of the
-// staged stream is bit 31 - (p % 32) of S[p / 32].  Decodes `count` codewords from bit `pos` on
-// and calls put(k, symbol) for k >= skip; returns the bit position after the last codeword.
+// Decoder for a bit stream staged in LDS.  Word k of the stream is S[kStagePad + k]; the words
+// from S[kStagePad - 1] to S[kStagePad + wmax + 2] are readable.  Decodes `count` codewords from
+// bit `pos` on and calls put(k, residual) for k >= skip; returns the bit position after the last
+// codeword.
 //
 // LDS reads at any bit position are cheap, so there is no bit window to carry along and refill:
-// every codeword is looked up from the two words around its own position.  The per-symbol
-// dependency chain is position -> word pair -> first-level table -> length -> position.
-// A corrupted stream cannot run out of the staged range: word indices are clamped to wmax.
+// every codeword is looked up from the two words around its own position.  The 32 bits from
+// position p on are alignbit(S[j], S[j+1], -p mod 32) with j = (p + 31) / 32 - 1 (stream words):
+// counted this way the shift stays below 32 also when p is a multiple of 32.
+// A corrupted stream cannot run out of the staged range: word indices are clamped.
+constexpr int kStagePad = 4;
 template <class PUT>
 __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint32_t *S, uint32_t wmax, uint32_t pos,
-                                               uint32_t count, uint32_t skip, uint32_t fallback_sym, PUT put,
-                                               bool &bad)
+                                               uint32_t count, uint32_t skip, PUT put, bool &bad)
 {
     const uint32_t t32 = T.t32, sh = T.sh, has_long = T.has_long;
-#pragma unroll 2
+    const uint32_t jmax = wmax + 1;
+    const char *t1 = reinterpret_cast<const char *>(T.t1);
+#pragma unroll 4
     for (uint32_t k = 0; k < count; ++k) {
-        uint32_t wi = pos >> 5;
-        wi = wi < wmax ? wi : wmax;
-        const uint32_t w0 = S[wi], w1 = S[wi + 1];
-        const uint32_t off = pos & 31;
-        const uint64_t w64 = ((((uint64_t)w0) << 32) | w1) << off;
-        const uint32_t hi = (uint32_t)(w64 >> 32);
-        uint32_t e = T.t1[hi >> (32 - kLB)];
+        uint32_t j = (pos + 31u) >> 5;                        // stream word j-1 holds bit pos (or ends just before it)
+        j = j < jmax ? j : jmax;
+        const uint32_t w0 = S[kStagePad - 1 + j], w1 = S[kStagePad + j];
+        const uint32_t hi = __builtin_amdgcn_alignbit(w0, w1, 0u - pos);
+        uint32_t e = *reinterpret_cast<const uint16_t *>(t1 + ((hi >> (31 - kLB)) & (2u * kT1Size - 2u)));
         if (e == 0) {
             if (has_long) {
                 uint32_t i2 = (hi - t32) >> sh;
@@ -355,9 +361,9 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
             }
             if (e == 0) {
                 // canonical search over the longer lengths on a 64-bit window
-                uint64_t v = w64;
-                if (off) v |= (uint64_t)(S[wi + 2] >> (32 - off));
-                uint32_t len = 0, sy = fallback_sym;
+                const uint32_t lo = __builtin_amdgcn_alignbit(w1, S[kStagePad + 1 + j], 0u - pos);
+                const uint64_t v = (((uint64_t)hi) << 32) | lo;
+                uint32_t len = 0, sy = 0;                     // no match: residual 0
                 for (uint32_t L = kLB + 1; L <= T.max_len; ++L) {
                     const uint64_t code = v >> (64 - L);
                     if (code >= T.first[L] && code - T.first[L] < T.count[L]) {
@@ -371,7 +377,7 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
             }
         }
         pos += e >> 10;
-        if (k >= skip) put(k, e & 1023u);
+        if (k >= skip) put(k, entry_residual(e));
     }
     return pos;
 }

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
     __shared__ DecodeTables T;
     __shared__ int32_t  Rs[kWaves][kBandMax + kND];       // one pad word per sub-block: lane-conflict free
     __shared__ uint32_t Ps[kWaves][kE * kWave + 2];       // exclusive prefix of sub-block bit counts
-    __shared__ __align__(16) uint32_t Ss[kWaves][kStageWords + 4];   // staged payload; after the decode, the lane records
+    __shared__ __align__(16) uint32_t Ss[kWaves][kStagePad + kStageWords + 4];   // staged payload; after the decode, the lane records
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
 #ifdef CMPZ_PHASE_CLOCKS
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
     uint2 *RC = reinterpret_cast<uint2 *>(S);
     const uint32_t payload_units = T.payload_units, n_outl = T.n_outliers;
 
-    const uint32_t W = a.W, H = a.H, HW = a.HW, R0 = a.radius;
+    const uint32_t W = a.W, H = a.H, HW = a.HW;
     const uint32_t *__restrict__ chunk_off = reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_chunk_off);
     const uint32_t *__restrict__ outl_off = reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_outl_off);
     const uint16_t *__restrict__ sub_bits = reinterpret_cast<const uint16_t *>(a.buf + a.lay.off_sub_bits);
@@ -249,8 +249,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         }
         const bool staged = sg.nq != 0;                  // uniform
         if (staged) {
-            if ((uint32_t)lane < sg.nq) reinterpret_cast<uint4 *>(S)[lane] = s0;
-            if ((uint32_t)lane + kWave < sg.nq) reinterpret_cast<uint4 *>(S)[lane + kWave] = s1;
+            if ((uint32_t)lane < sg.nq) reinterpret_cast<uint4 *>(S + kStagePad)[lane] = s0;
+            if ((uint32_t)lane + kWave < sg.nq) reinterpret_cast<uint4 *>(S + kStagePad)[lane + kWave] = s1;
         }
         wave_sync();
         PHASE(1)
@@ -296,9 +296,9 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
                     reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_payload + (uint64_t)uu0 * 16);
                 auto run_decode = [&](uint32_t count, uint32_t skip, auto put) -> uint32_t {
                     if (staged)
-                        return decode_lds(T, S, sg.nq * 4 - 1, spos, count, skip, R0, put, lbad) - spos + start;
+                        return decode_lds(T, S, sg.nq * 4 - 1, spos, count, skip, put, lbad) - spos + start;
                     return decode_run<false>(T, [&](uint32_t k) -> uint32_t { return gw[k < last ? k : last]; }, start,
-                                             count, skip, R0, put, lbad);
+                                             count, skip, put, lbad);
                 };
                 if (SUB == 32 && n_here == 32u && folded) {
                     // complete 32-codeword sub-block: the row starts as a bit mask; all 32 slots of
@@ -308,9 +308,10 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
                     my_reset = k0 < 32u ? k0 : (uint32_t)SUB;
                     for (; k0 < 32u; k0 += W) mask |= 1u << k0;
                     int32_t run = 0;
-                    end = run_decode(32u, 0u, [&](uint32_t k, uint32_t sy) {
-                        const int32_t keep = ~__builtin_amdgcn_sbfe((int)mask, k, 1);     // 0 where the row restarts
-                        run = (run & keep) + ((int32_t)sy - (int32_t)R0);
+                    const uint32_t keep_mask = ~mask;
+                    end = run_decode(32u, 0u, [&](uint32_t k, int32_t d) {
+                        const int32_t keep = __builtin_amdgcn_sbfe((int)keep_mask, k, 1); // 0 where the row restarts
+                        run = (run & keep) + d;
                         my[k] = run;
                     });
                     my_tail = my[khi - 1];
@@ -319,8 +320,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
                     uint32_t w = w_first;
                     int32_t run = 0;
                     uint32_t first_reset = (uint32_t)SUB;
-                    end = run_decode(khi, klo, [&](uint32_t k, uint32_t sy) {
-                        const int32_t d = (int32_t)sy - (int32_t)R0;
+                    end = run_decode(khi, klo, [&](uint32_t k, int32_t d) {
                         if (w == 0) { run = 0; first_reset = first_reset < k ? first_reset : k; }
                         run += d;
                         my[k] = run;
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
                 } else {
                     const bool whole = (SUB == 32 && n_here == 32u);
                     end = run_decode(whole ? 32u : khi, whole ? 0u : klo,
-                                     [&](uint32_t k, uint32_t sy) { my[k] = (int32_t)sy - (int32_t)R0; });
+                                     [&](uint32_t k, int32_t d) { my[k] = d; });
                 }
             }
             // a sub-block decoded to its end must land exactly on its stored bit count

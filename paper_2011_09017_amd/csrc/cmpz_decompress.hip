@@ -125,7 +125,7 @@ __global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, Decode
 
     // symbols ordered by (length, symbol)
     const uint32_t rank = rank_within_length(L, wave_cnt, tid);
-    if (L) T.sorted[offs[L] + rank] = (uint16_t)tid;
+    if (L) T.sorted[offs[L] + rank] = (uint16_t)(((uint32_t)tid - a.radius) & 1023u);   // as a residual
     if (tid < 64) { T.first[tid] = first_code[tid]; T.count[tid] = bl_count[tid]; T.offs[tid] = offs[tid]; }
     __syncthreads();
 
@@ -177,14 +177,13 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecompressArgs a, const 
 {
     constexpr int kStride = SUB + 2;                       // u16 units; (SUB+2)/2 words is odd
     __shared__ DecodeTables T;
-    __shared__ uint16_t stage[kDecThreads * kStride];
+    __shared__ int16_t stage[kDecThreads * kStride];
     if (a.meta[kMetaBad]) return;
     const int tid = threadIdx.x;
     load_tables(T, tb, tid, kDecThreads);
     __syncthreads();
 
     constexpr uint32_t nsub = kChunk / SUB;
-    const uint32_t R = a.radius;
     const uint64_t g = (uint64_t)blockIdx.x * kDecThreads + tid;      // global sub-block index
     const uint32_t c = (uint32_t)(g / nsub), j = (uint32_t)(g % nsub);
     const uint64_t e0 = g * SUB;                                    // first element of the sub-block
@@ -204,12 +203,12 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecompressArgs a, const 
         for (uint32_t k = 0; k < j; ++k) start += sub_bits[k];
         const uint32_t sb = sub_bits[j];
         if ((uint64_t)start + sb > (uint64_t)nwords * 32) { bad = true; nwords = 0; }
-        uint16_t *my = stage + tid * kStride;
+        int16_t *my = stage + tid * kStride;
         uint32_t end = 0;
         if (nwords) {
             const uint32_t last = nwords - 1;
-            end = decode_run<false>(T, [&](uint32_t k) -> uint32_t { return words[k < last ? k : last]; }, start, n_here, 0u, R,
-                             [&](uint32_t k, uint32_t sy) { my[k] = (uint16_t)sy; }, bad);
+            end = decode_run<false>(T, [&](uint32_t k) -> uint32_t { return words[k < last ? k : last]; }, start, n_here, 0u,
+                             [&](uint32_t k, int32_t d) { my[k] = (int16_t)d; }, bad);
         }
         if (end != start + sb) bad = true;
     }
@@ -222,8 +221,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecompressArgs a, const 
     for (uint32_t e = tid; e < (uint32_t)(kDecThreads * SUB); e += kDecThreads) {
         const uint64_t i = tile0 + e;
         if (i >= a.numel) break;
-        const uint32_t s = stage[(e / SUB) * kStride + (e % SUB)];
-        out[i] = (int32_t)s - (int32_t)R;
+        out[i] = stage[(e / SUB) * kStride + (e % SUB)];
     }
 }
 
