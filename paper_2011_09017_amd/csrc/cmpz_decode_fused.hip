@@ -28,6 +28,8 @@
 // decode of the current one, and its payload during the column pass.
 #include "cmpz_decode_core.h"
 
+#include <type_traits>
+
 namespace cmpz {
 namespace {
 
@@ -91,7 +93,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
     __shared__ uint32_t Ps[kWaves][kE * kWave + 2];       // exclusive prefix of sub-block bit counts
     __shared__ __align__(16) uint32_t Ss[kWaves][kStagePad + kStageWords + 4];   // staged payload; after the decode, the lane records
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);     // tells the compiler that it is uniform in the wave
 #ifdef CMPZ_PHASE_CLOCKS
     long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = clock64();
@@ -131,6 +134,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         uint32_t v[kE], uu0, uu1, olo, ohi, cf, cl, cl1;
     };
 
+    const uint32_t vzero = __builtin_amdgcn_mbcnt_lo(0u, 0u);    // 0, but not known to be uniform
     auto band_of = [&](uint32_t item, uint32_t b) -> Band {
         Band g;
         g.valid = item < pl.nitems;
@@ -164,11 +168,13 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
             const uint32_t c = (sb0 + lane) / kNSub;
             f.uu0 = chunk_off[c]; f.uu1 = chunk_off[c + 1];
         }
-        f.olo = outl_off[g.e0 / kChunk];
-        f.ohi = outl_off[(g.e0 + g.n - 1) / kChunk + 1];
-        f.cf = chunk_off[sb0 / kNSub];
-        f.cl = chunk_off[sb1 / kNSub];
-        f.cl1 = chunk_off[sb1 / kNSub + 1];
+        // uniform values, but fetched with vector loads: scalar loads share their counter with LDS
+        // traffic and return out of order, so waiting for one would drain every LDS access in flight
+        f.olo = outl_off[g.e0 / kChunk + vzero];
+        f.ohi = outl_off[(g.e0 + g.n - 1) / kChunk + 1 + vzero];
+        f.cf = chunk_off[sb0 / kNSub + vzero];
+        f.cl = chunk_off[sb1 / kNSub + vzero];
+        f.cl1 = chunk_off[sb1 / kNSub + 1 + vzero];
         return f;
     };
     // exclusive prefix of a band's bit counts from the start of its first chunk
@@ -192,10 +198,12 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         const uint32_t j0 = sb0 & (kNSub - 1), jl = sb1 & (kNSub - 1), idxl = j0 + (sb1 - sb0);
         const uint32_t first_bit = P[j0] - P[0];                 // in the first chunk's stream
         const uint32_t end_bit = P[idxl + 1] - P[idxl - jl];     // in the last chunk's stream
-        if (!(f.cf <= f.cl && f.cl <= f.cl1 && f.cl1 <= payload_units)) return st;
-        const uint64_t w_lo = (uint64_t)f.cf * 4 + (first_bit >> 5);
-        const uint64_t w_hi = (uint64_t)f.cl * 4 + ((uint64_t)end_bit + 31) / 32;
-        if (w_hi > (uint64_t)f.cl1 * 4 || w_hi <= w_lo) return st;
+        const uint32_t cf = __builtin_amdgcn_readfirstlane(f.cf), cl = __builtin_amdgcn_readfirstlane(f.cl),
+                       cl1 = __builtin_amdgcn_readfirstlane(f.cl1);
+        if (!(cf <= cl && cl <= cl1 && cl1 <= payload_units)) return st;
+        const uint64_t w_lo = (uint64_t)cf * 4 + (first_bit >> 5);
+        const uint64_t w_hi = (uint64_t)cl * 4 + ((uint64_t)end_bit + 31) / 32;
+        if (w_hi > (uint64_t)cl1 * 4 || w_hi <= w_lo) return st;
         const uint64_t q0 = w_lo >> 2, q1 = (w_hi + 3) >> 2;
         if (q1 - q0 > (uint64_t)(kStageWords / 4)) return st;
         st.q0 = (uint32_t)q0; st.nq = (uint32_t)(q1 - q0);
@@ -256,7 +264,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         PHASE(1)
 
         // outliers of the band: a range of the outlier list (filtered by index below)
-        uint32_t olo = fa.olo, ohi = fa.ohi;
+        uint32_t olo = __builtin_amdgcn_readfirstlane(fa.olo), ohi = __builtin_amdgcn_readfirstlane(fa.ohi);
         if (olo > ohi || ohi > n_outl) { bad = true; olo = ohi = 0; }
         const bool folded = (olo == ohi);                // uniform: no outliers, rows are summed while decoding
 
@@ -390,11 +398,15 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         // ---- column prefix sums (adding the lanes' carries); wide rows are de-quantised and stored from here ----
         const bool direct = W >= 32;                     // a wave then stores runs of >= 128 bytes
         const uint32_t nrow = pl.big ? rows : H;
-        auto walk = [&](uint32_t col, int32_t acc) -> int32_t {
+        // byte offsets from the band's first output element: the stores then take a uniform base
+        // and a 32-bit offset per lane
+        char *__restrict__ band_out = reinterpret_cast<char *>(a.xout + e0);
+        auto walk = [&](auto direct_c, uint32_t col, int32_t acc) -> int32_t {
+            constexpr bool kDirect = decltype(direct_c)::value;
             const uint32_t p = pl.big ? 0u : pl.divW.div(col);
             const uint32_t w = col - p * W;
             uint32_t u = p * HW + w + u0;
-            float *__restrict__ dst = a.xout + e0 + p * HW + w;
+            uint32_t off = (p * HW + w) * 4u;
             uint32_t h = 0;
             for (; h + 8 <= nrow; h += 8) {              // 8 rows at a time: loads in flight together
                 int32_t t8[8];
@@ -409,28 +421,33 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {
                     acc += t8[q] + ((kk[q] < rc[q].x) ? (int32_t)rc[q].y : 0);
-                    if (direct) dst[(h + q) * W] = (float)acc * s; else R[ph[q]] = acc;
+                    if (kDirect) *reinterpret_cast<float *>(band_out + (off + q * 4u * W)) = (float)acc * s;
+                    else R[ph[q]] = acc;
                 }
                 u += 8 * W;
+                off += 32u * W;
             }
-            for (; h < nrow; ++h, u += W) {
+            for (; h < nrow; ++h, u += W, off += 4u * W) {
                 const uint32_t t = u >> kLog, ph = u + t;
                 const uint2 rc = RC[t];
                 acc += R[ph] + (((u & (uint32_t)(SUB - 1)) < rc.x) ? (int32_t)rc.y : 0);
-                if (direct) dst[h * W] = (float)acc * s; else R[ph] = acc;
+                if (kDirect) *reinterpret_cast<float *>(band_out + off) = (float)acc * s; else R[ph] = acc;
             }
             return acc;
         };
-        if (pl.big) {
+        auto walk_all = [&](auto direct_c) {
+            if (pl.big) {
 #pragma unroll
-            for (int c = 0; c < kColGroups; ++c) {
-                const uint32_t col = c * kWave + lane;
-                if (col < W) colacc[c] = walk(col, colacc[c]);
+                for (int c = 0; c < kColGroups; ++c) {
+                    const uint32_t col = c * kWave + lane;
+                    if (col < W) colacc[c] = walk(direct_c, col, colacc[c]);
+                }
+            } else {
+                const uint32_t ncols = npl * W;
+                for (uint32_t col = lane; col < ncols; col += kWave) (void)walk(direct_c, col, 0);
             }
-        } else {
-            const uint32_t ncols = npl * W;
-            for (uint32_t col = lane; col < ncols; col += kWave) (void)walk(col, 0);
-        }
+        };
+        if (direct) walk_all(std::true_type{}); else walk_all(std::false_type{});
 
         // ---- narrow rows: de-quantise and store from LDS, 128 bits at a time ----
         if (!direct) {
