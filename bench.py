@@ -52,7 +52,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg5_resnet18_stream")
     ap.add_argument("--eb", type=float, default=None)
     ap.add_argument("--sub", type=int, default=32, help="codes per sub-block (decode parallelism vs. 16 bits of metadata each)")
-    ap.add_argument("--streams", type=int, default=2, help="contexts/streams the tensors are dealt over, round robin")
+    ap.add_argument("--streams", type=int, default=3, help="contexts/streams the tensors are dealt over, round robin")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=2, help="tensors of the workload the oracle is timed on")
     args = ap.parse_args()

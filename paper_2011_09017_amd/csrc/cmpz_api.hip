@@ -140,7 +140,7 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
 
     uint64_t off = 0;
     auto carve = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, 256); return o; };
-    const uint64_t o_sym = carve(2 * (c.max_numel + 16));
+    const uint64_t o_sym = carve(2 * (ctx->max_chunks * c.chunk + 16));   // whole chunks: readable past numel
     const uint64_t o_hist = carve(4 * kMaxSym * kHistCopies);
     const uint64_t o_hist_copy = carve(4 * kMaxSym);
     const uint64_t o_desc = carve(8 * (ctx->max_chunks + 1));

@@ -237,12 +237,16 @@ __device__ __forceinline__ uint64_t look_back(const uint64_t *desc, uint32_t c, 
 // ---------------------------------------------------------------------------
 // Sweep 2: chunked Huffman bit-packing with the bit offsets found on the fly.
 // Workgroups take tiles of up to 8 consecutive chunks in index order from a
-// ticket counter.  A tile's symbols are loaded once and stay in registers: first
-// their code lengths are summed (sub_bits, chunk sizes, the tile's size, which is
-// published at once), then each chunk is packed into a zeroed LDS image (bit k
-// of the chunk is bit 31-(k%32) of little-endian word k/32) and copied out with
-// 128-bit stores at the offset that wave 0 finds meanwhile by look-back.  The
-// workgroup that finishes last writes the header.
+// ticket counter.  First the code lengths of a tile's symbols are summed
+// (sub_bits, chunk sizes, the tile's size, which is published at once), then the
+// symbols are read again (from L2) and each chunk is packed into a zeroed LDS
+// image (bit k of the chunk is bit 31-(k%32) of little-endian word k/32), which
+// is copied out with 128-bit stores at the offset that wave 0 finds meanwhile by
+// look-back.  While no codeword is longer than 27 bits (the usual case) a table
+// entry is the left-aligned code with its length in the low bits, and a codeword
+// is OR-ed into the image at its own bit position with two LDS atomics; longer
+// codes go through a 64-bit accumulator.  The workgroup that finishes last writes
+// the header.
 // ---------------------------------------------------------------------------
 constexpr uint32_t kChunkImageWords = kChunk * kMaxCodeLen / 32;   // 6144 words = 24 KB
 constexpr int kTileMax = 8;
@@ -271,21 +275,21 @@ __device__ __forceinline__ void append_bits(uint32_t *img, uint64_t &acc, uint32
     }
 }
 
-// The symbols of a tile live in registers, chunk q in slot q.  The per-chunk loops below run
-// un-unrolled over slot 0 and rotate the slots after each chunk, so the loop body exists once
-// and register use stays bounded.
+// Per-chunk state of a tile lives in registers, chunk q in slot q.  The per-chunk loops below run
+// un-unrolled over slot 0 and rotate the slots after each chunk, so the loop body exists once.
 struct TileRegs {
-    uint4    sv[kTileMax][2];        // 16 symbols per chunk (u16 pairs); 0xffff = past the end
     uint32_t pos[kTileMax];          // this thread's bit offset inside each chunk
     __device__ __forceinline__ void rotate()
     {
-        const uint4 a0 = sv[0][0], a1 = sv[0][1];
         const uint32_t p = pos[0];
 #pragma unroll
-        for (int q = 0; q + 1 < kTileMax; ++q) { sv[q][0] = sv[q + 1][0]; sv[q][1] = sv[q + 1][1]; pos[q] = pos[q + 1]; }
-        sv[kTileMax - 1][0] = a0; sv[kTileMax - 1][1] = a1; pos[kTileMax - 1] = p;
+        for (int q = 0; q + 1 < kTileMax; ++q) pos[q] = pos[q + 1];
+        pos[kTileMax - 1] = p;
     }
 };
+
+constexpr uint32_t kPastEnd  = kMaxSym;      // symbol value of elements past the end of the tensor (codes to nothing)
+constexpr uint32_t kShortMax = 27;           // longest codeword the 32-bit table entries can hold
 
 #ifdef CMPZ_PHASE_CLOCKS
 #define PHASE(k) if (tid == 0) { const long long now_ = clock64(); clk[k] += now_ - last_; last_ = now_; }
@@ -299,8 +303,8 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
     long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = clock64();
 #endif
-    __shared__ uint64_t table[kMaxSym];              // length << 56 | code
-    __shared__ __align__(16) uint32_t image[kChunkImageWords];
+    __shared__ uint64_t table[kMaxSym + 1];          // length << 56 | code; or, as 32-bit words, code << (32 - length) | length
+    __shared__ __align__(16) uint32_t image[kChunkImageWords + 4];
     __shared__ uint32_t wave_bits[kThreads / kWave][kTileMax];
     __shared__ uint32_t s_units[kTileMax];
     __shared__ uint32_t s_tile;
@@ -314,7 +318,14 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
     const uint32_t group = a.sub / 16;               // lanes per sub-block: 2, 4 or 8
     const uint32_t *len_word = reinterpret_cast<const uint32_t *>(table) + 1;   // high words: length << 24 | ...
 
-    for (int k = tid; k < (int)kMaxSym; k += kThreads) table[k] = a.codes[k];
+    uint32_t *table32 = reinterpret_cast<uint32_t *>(table);
+    const bool short_codes = a.meta[kMetaMaxLen] <= kShortMax;       // uniform; written by the codebook kernel
+    for (int k = tid; k <= (int)kMaxSym; k += kThreads) {
+        const uint64_t e = (k < (int)kMaxSym) ? a.codes[k] : 0ull;
+        const uint32_t len = (uint32_t)(e >> 56);
+        if (short_codes) table32[k] = len ? (((uint32_t)e << (32u - len)) | len) : 0u;
+        else table[k] = e;
+    }
     uint64_t my_bits = 0;                            // thread 0: bits of the chunks this workgroup packed
     bool failed = false;
     TileRegs r;
@@ -329,54 +340,61 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
         const uint32_t c0 = t * tc;
         const uint32_t nq = (nchunks - c0 < tc) ? nchunks - c0 : tc;     // chunks in this tile
 
-        // ---- all symbols of the tile, issued together ----
-#pragma unroll
-        for (int q = 0; q < kTileMax; ++q) {
-            r.pos[q] = 0;
-            r.sv[q][0] = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
-            r.sv[q][1] = r.sv[q][0];
-            if (q < (int)nq) {
-                const uint64_t i0 = (uint64_t)(c0 + q) * kChunk + (uint64_t)tid * 16;
-                if (i0 + 16 <= a.numel) {
-                    r.sv[q][0] = *reinterpret_cast<const uint4 *>(a.sym + i0);
-                    r.sv[q][1] = *reinterpret_cast<const uint4 *>(a.sym + i0 + 8);
-                } else {
-                    uint32_t w[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const uint32_t lo = (i0 + 2 * j < a.numel) ? a.sym[i0 + 2 * j] : 0xffffu;
-                        const uint32_t hi = (i0 + 2 * j + 1 < a.numel) ? a.sym[i0 + 2 * j + 1] : 0xffffu;
-                        w[j] = lo | (hi << 16);
-                    }
-                    r.sv[q][0] = make_uint4(w[0], w[1], w[2], w[3]);
-                    r.sv[q][1] = make_uint4(w[4], w[5], w[6], w[7]);
-                }
+        // 16 symbols of chunk c for this thread; elements past the end read as kPastEnd (the
+        // symbol buffer holds whole chunks, so the loads themselves are always in bounds)
+        auto load_syms = [&](uint32_t c, uint4 &lo, uint4 &hi) {
+            const uint64_t i0 = (uint64_t)c * kChunk + (uint64_t)tid * 16;
+            lo = *reinterpret_cast<const uint4 *>(a.sym + i0);
+            hi = *reinterpret_cast<const uint4 *>(a.sym + i0 + 8);
+            if (i0 + 16 > a.numel) {
+                const uint32_t valid = (i0 < a.numel) ? (uint32_t)(a.numel - i0) : 0u;   // < 16
+                auto fix = [&](uint32_t w, uint32_t j) -> uint32_t {                      // word j holds elements 2j, 2j+1
+                    if (2 * j >= valid) return kPastEnd | (kPastEnd << 16);
+                    if (2 * j + 1 >= valid) return (w & 0xffffu) | (kPastEnd << 16);
+                    return w;
+                };
+                lo = make_uint4(fix(lo.x, 0), fix(lo.y, 1), fix(lo.z, 2), fix(lo.w, 3));
+                hi = make_uint4(fix(hi.x, 4), fix(hi.y, 5), fix(hi.z, 6), fix(hi.w, 7));
             }
-        }
-
+        };
+#pragma unroll
+        for (int q = 0; q < kTileMax; ++q) r.pos[q] = 0;
+        // sums the code lengths of this thread's 16 symbols of chunk c0+q: sub-block bit counts,
+        // the thread's bit offset within its wave, the wave's total
+        auto lens_chunk = [&](int q, const uint4 &lo, const uint4 &hi, uint32_t &pos_out) {
+            uint32_t bits = 0;
+            if (short_codes) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) bits += table32[sym_at(lo, hi, j)] & 31u;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) bits += len_word[2 * sym_at(lo, hi, j)] >> 24;
+            }
+            const uint32_t inc = wave_inclusive_sum(bits);
+            const uint32_t exc = inc - bits;
+            // the first lane of a sub-block sits group-1 lanes below its last lane, in the same DPP row
+            const uint32_t first_exc = (group == 8) ? row_shr<0x117>(exc) : (group == 4) ? row_shr<0x113>(exc)
+                                                                                          : row_shr<0x111>(exc);
+            if ((tid & (group - 1)) == group - 1)
+                sub_bits[(uint64_t)(c0 + q) * a.lay.nsub + tid / group] = (uint16_t)(inc - first_exc);
+            pos_out = exc;                           // completed below with the lower waves' bits
+            if (lane == 63) wave_bits[wv][q] = inc;
+        };
+        uint4 lo, hi, nlo, nhi;                      // one chunk at a time; the tile is read again for the packing
+        load_syms(c0, lo, hi);
+        nlo = lo; nhi = hi;
         PHASE(1)
-        // ---- code lengths: per-thread sums, sub-block sums, per-wave sums ----
 #pragma unroll 1
         for (int q = 0; q < kTileMax; ++q) {
             if (q < (int)nq) {
-                uint32_t bits = 0;
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const uint32_t sy = sym_at(r.sv[0][0], r.sv[0][1], j);
-                    bits += (sy != 0xffffu) ? (len_word[2 * sy] >> 24) : 0u;
-                }
-                const uint32_t inc = wave_inclusive_sum(bits);
-                const uint32_t exc = inc - bits;
-                // the first lane of a sub-block sits group-1 lanes below its last lane, in the same DPP row
-                const uint32_t first_exc = (group == 8) ? row_shr<0x117>(exc) : (group == 4) ? row_shr<0x113>(exc)
-                                                                                              : row_shr<0x111>(exc);
-                if ((tid & (group - 1)) == group - 1)
-                    sub_bits[(uint64_t)(c0 + q) * a.lay.nsub + tid / group] = (uint16_t)(inc - first_exc);
-                r.pos[0] = exc;                      // completed below with the lower waves' bits
-                if (lane == 63) wave_bits[wv][q] = inc;
+                if (q + 1 < (int)nq) load_syms(c0 + q + 1, nlo, nhi);    // in flight during this chunk
+                lens_chunk(q, lo, hi, r.pos[0]);
+                lo = nlo; hi = nhi;
             }
             r.rotate();
         }
+        load_syms(c0, lo, hi);                       // second read of the tile (L2), for the packing below
+        nlo = lo; nhi = hi;
         __syncthreads();
         uint32_t tile_units = 0;
 #pragma unroll
@@ -445,38 +463,54 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
         };
         zero_image();
         __syncthreads();                             // also makes s_units visible
+        // packs chunk c0+q into the image at this thread's bit offset pos_q
+        auto pack_chunk = [&](int q, const uint4 &lo, const uint4 &hi, uint32_t pos_q) {
+            const uint32_t uq = s_units[q];
+            if (uq > kImageUnits) { failed = true; return; }          // cannot happen for counts below 2^32
+            if (u_img + uq > kImageUnits) {          // image full: store it and start afresh
+                __syncthreads();
+                store_image();
+                __syncthreads();
+                zero_image();
+                __syncthreads();
+            }
+            if (tid == 0) chunk_off[c0 + q] = (uint32_t)(s_excl >> 32) + u_done + u_img;
+            const uint32_t p0 = u_img * 128u + pos_q;                 // bit position in the image
+            if (short_codes) {
+                uint32_t pos = p0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const uint32_t e = table32[sym_at(lo, hi, j)];
+                    const uint32_t code = e & ~31u, o = pos & 31u;    // left-aligned code
+                    uint32_t *w = image + (pos >> 5);
+                    atomicOr(w, code >> o);
+                    atomicOr(w + 1, __builtin_amdgcn_alignbit(code, 0u, o));   // the part that spills over
+                    pos += e & 31u;
+                }
+            } else {
+                uint32_t wi = p0 >> 5, fill = p0 & 31;
+                uint64_t acc = 0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const uint64_t cw = table[sym_at(lo, hi, j)];
+                    uint32_t len = (uint32_t)(cw >> 56);
+                    if (len > 32) {                                   // rare: split off the high part
+                        append_bits(image, acc, fill, wi, (uint32_t)((cw & 0x00ffffffffffffffull) >> 32), len - 32);
+                        len = 32;
+                    }
+                    append_bits(image, acc, fill, wi, (uint32_t)cw, len);
+                }
+                if (fill && (uint32_t)(acc >> 32)) atomicOr(&image[wi], (uint32_t)(acc >> 32));
+            }
+            u_img += uq;
+            left -= uq;
+        };
 #pragma unroll 1
         for (int q = 0; q < kTileMax; ++q) {
             if (q < (int)nq) {                       // uniform
-                const uint32_t uq = s_units[q];
-                if (uq > kImageUnits) { failed = true; }              // cannot happen for counts below 2^32
-                else {
-                    if (u_img + uq > kImageUnits) {  // image full: store it and start afresh
-                        __syncthreads();
-                        store_image();
-                        __syncthreads();
-                        zero_image();
-                        __syncthreads();
-                    }
-                    if (tid == 0) chunk_off[c0 + q] = (uint32_t)(s_excl >> 32) + u_done + u_img;   // s_excl: see below
-                    const uint32_t p0 = u_img * 128u + r.pos[0];      // bit position in the image
-                    uint32_t wi = p0 >> 5, fill = p0 & 31;
-                    uint64_t acc = 0;
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const uint32_t sy = sym_at(r.sv[0][0], r.sv[0][1], j);
-                        const uint64_t cw = (sy != 0xffffu) ? table[sy] : 0ull;
-                        uint32_t len = (uint32_t)(cw >> 56);
-                        if (len > 32) {                                 // rare: split off the high part
-                            append_bits(image, acc, fill, wi, (uint32_t)((cw & 0x00ffffffffffffffull) >> 32), len - 32);
-                            len = 32;
-                        }
-                        append_bits(image, acc, fill, wi, (uint32_t)cw, len);
-                    }
-                    if (fill && (uint32_t)(acc >> 32)) atomicOr(&image[wi], (uint32_t)(acc >> 32));
-                    u_img += uq;
-                    left -= uq;
-                }
+                if (q + 1 < (int)nq) load_syms(c0 + q + 1, nlo, nhi);
+                pack_chunk(q, lo, hi, r.pos[0]);
+                lo = nlo; hi = nhi;
             }
             r.rotate();
         }

@@ -148,6 +148,30 @@ def test_adversarial_values(gpu, orc):
     assert h["n_outliers"] > n // 2
 
 
+@pytest.mark.parametrize("nsym", [30, 36])
+def test_long_codewords(gpu, orc, nsym):
+    """Residual counts that follow the Fibonacci numbers give a maximally skewed tree: the longest
+    codeword has nsym - 1 bits (29: past the short-code packing of the encoder; 35: past 32 bits)."""
+    eb = 1e-2
+    _, _, s, _ = orc.constants(eb)
+    fib = [1, 1]
+    while len(fib) < nsym:
+        fib.append(fib[-1] + fib[-2])
+    vals = np.array([(k + 1) // 2 * (1 if k % 2 else -1) for k in range(nsym)], np.int64)   # 0, 1, -1, 2, -2, ...
+    counts = np.array(fib[::-1], np.int64)                   # residual 0 is the most frequent
+    n = int(counts.sum())
+    pad = (-n) % 64
+    counts[0] += pad
+    d = np.repeat(vals, counts)
+    np.random.default_rng(nsym).shuffle(d)
+    q = np.cumsum(d.reshape(-1, 64), axis=1)                 # rows of 64, one row per plane: 1D Lorenzo
+    assert np.abs(q).max() < 16384
+    x = (q.astype(np.float32) * np.float32(s)).reshape(1, -1, 1, 64)
+    ctx = make_ctx(gpu, max_numel=x.size)
+    h = check_case(gpu, orc, x, eb, ctx, orc.Config(), stages=True)
+    assert h["max_len"] == nsym - 1
+
+
 def test_nan_inf_out_of_range(gpu, orc):
     ctx = make_ctx(gpu)
     x = activation((1, 4, 40, 40), seed=3).numpy()
