@@ -650,7 +650,11 @@ void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st)
         launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist, dim3(tiles), dim3(kThreads), st, a);
     launch_codebook(a, prof, st);
     const uint32_t ntiles = (nchunks + a.tile_chunks - 1) / a.tile_chunks;
-    const uint32_t egrid = ntiles < 256u * 4u ? ntiles : 256u * 4u;
+    // every workgroup costs a ticket, a look-back over the tiles in flight and a code table load:
+    // about one workgroup per 16 chunks, between one and four per CU
+    uint32_t egrid = nchunks / 16;
+    egrid = egrid < 256u ? 256u : egrid > 1024u ? 1024u : egrid;
+    egrid = egrid < ntiles ? egrid : ntiles;
     launch(prof, kKEncode, k_encode, dim3(egrid), dim3(kThreads), st, a);
     launch(prof, kKOutliers, k_outliers, dim3(nchunks), dim3(kThreads), st, a);
 }
