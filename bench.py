@@ -15,7 +15,8 @@ ONE JSON line.
   roofline   = the kernel with the largest share of the step: its algorithmic
                HBM bytes per second against the 8 TB/s peak, durations measured
                with HIP events around each of its launches (a second pass over
-               the same steps, so that the events do not perturb `value`)
+               the same steps, one call at a time, so that the events do not
+               perturb `value` and concurrent streams do not stretch a kernel)
   cpu_baseline = the CPU oracle, one core, on a bounded sample of the workload
 """
 from __future__ import annotations
@@ -54,6 +55,9 @@ def main() -> int:
     ap.add_argument("--sub", type=int, default=32, help="codes per sub-block (decode parallelism vs. 16 bits of metadata each)")
     ap.add_argument("--streams", type=int, default=3, help="contexts/streams the tensors are dealt over, round robin")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain device copy of tensor 0 (numel*4 bytes read and written): "
+                         "the known traffic against which hardware counter readings are scaled")
     ap.add_argument("--cpu-sample", type=int, default=2, help="tensors of the workload the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -106,6 +110,9 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calib_copy:
+        outs[0].copy_(xs[0])
+        torch.cuda.synchronize()
     for k in range(S):
         st = ctxs[k].last_status(streams[k])
         assert st == 0, binding.cmp_strerror(st)
@@ -142,10 +149,21 @@ def main() -> int:
     tc /= args.steps; td /= args.steps
 
     # ---- per-kernel durations (events around every launch), same K steps ----------------
+    # One call at a time (a device-wide wait after each), so that a kernel's duration is its own
+    # and not that of whatever another stream ran beside it.
     for c in ctxs:
         c.profile(True)
     for _ in range(args.steps):
-        step()
+        for i in order:
+            rc, _ = binding.cmp_compress(ctxs[i % S]._h, xs[i].data_ptr(), xs[i].shape, eb, arena[i].data_ptr(),
+                                         arena[i].numel(), False, streams[i % S])
+            assert rc == 0, binding.cmp_strerror(rc)
+            torch.cuda.synchronize()
+        for i in reversed(order):
+            rc = binding.cmp_decompress(ctxs[i % S]._h, arena[i].data_ptr(), bounds[i], xs[i].shape, eb,
+                                        outs[i].data_ptr(), streams[i % S])
+            assert rc == 0, binding.cmp_strerror(rc)
+            torch.cuda.synchronize()
     kern = {}
     for k, c in enumerate(ctxs):
         for name, (ms, launches) in c.profile_read(streams[k]).items():

@@ -238,15 +238,15 @@ __device__ __forceinline__ uint64_t look_back(const uint64_t *desc, uint32_t c, 
 // Sweep 2: chunked Huffman bit-packing with the bit offsets found on the fly.
 // Workgroups take tiles of up to 8 consecutive chunks in index order from a
 // ticket counter.  First the code lengths of a tile's symbols are summed
-// (sub_bits, chunk sizes, the tile's size, which is published at once), then the
-// symbols are read again (from L2) and each chunk is packed into a zeroed LDS
-// image (bit k of the chunk is bit 31-(k%32) of little-endian word k/32), which
-// is copied out with 128-bit stores at the offset that wave 0 finds meanwhile by
-// look-back.  While no codeword is longer than 27 bits (the usual case) a table
-// entry is the left-aligned code with its length in the low bits, and a codeword
-// is OR-ed into the image at its own bit position with two LDS atomics; longer
-// codes go through a 64-bit accumulator.  The workgroup that finishes last writes
-// the header.
+// (sub_bits, chunk sizes, the tile's size, which is published at once), then
+// each chunk is packed into a zeroed LDS image (bit k of the chunk is bit
+// 31-(k%32) of little-endian word k/32), which is copied out with 128-bit stores
+// at the offset that wave 0 finds meanwhile by look-back.  While no codeword is
+// longer than 27 bits (the usual case) the tile's symbols stay in registers
+// between the two passes, a table entry is the left-aligned code with its length
+// in the low bits, and a codeword is OR-ed into the image at its own bit position
+// with two LDS atomics; longer codes take a slower path (symbols read twice, a
+// 64-bit accumulator).  The workgroup that finishes last writes the header.
 // ---------------------------------------------------------------------------
 constexpr uint32_t kChunkImageWords = kChunk * kMaxCodeLen / 32;   // 6144 words = 24 KB
 constexpr int kTileMax = 8;
@@ -380,21 +380,31 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
             pos_out = exc;                           // completed below with the lower waves' bits
             if (lane == 63) wave_bits[wv][q] = inc;
         };
-        uint4 lo, hi, nlo, nhi;                      // one chunk at a time; the tile is read again for the packing
-        load_syms(c0, lo, hi);
-        nlo = lo; nhi = hi;
-        PHASE(1)
+        uint4 sv[kTileMax][2];                       // short codes: the tile's symbols stay in registers
+        uint4 lo, hi, nlo, nhi;                      // long codes: one chunk at a time, read again for the packing
+        if (short_codes) {
+#pragma unroll
+            for (int q = 0; q < kTileMax; ++q)
+                if (q < (int)nq) load_syms(c0 + q, sv[q][0], sv[q][1]);      // all in flight together
+            PHASE(1)
+#pragma unroll
+            for (int q = 0; q < kTileMax; ++q)
+                if (q < (int)nq) lens_chunk(q, sv[q][0], sv[q][1], r.pos[q]);
+        } else {
+            load_syms(c0, lo, hi);
+            nlo = lo; nhi = hi;
 #pragma unroll 1
-        for (int q = 0; q < kTileMax; ++q) {
-            if (q < (int)nq) {
-                if (q + 1 < (int)nq) load_syms(c0 + q + 1, nlo, nhi);    // in flight during this chunk
-                lens_chunk(q, lo, hi, r.pos[0]);
-                lo = nlo; hi = nhi;
+            for (int q = 0; q < kTileMax; ++q) {
+                if (q < (int)nq) {
+                    if (q + 1 < (int)nq) load_syms(c0 + q + 1, nlo, nhi);    // in flight during this chunk
+                    lens_chunk(q, lo, hi, r.pos[0]);
+                    lo = nlo; hi = nhi;
+                }
+                r.rotate();
             }
-            r.rotate();
+            load_syms(c0, lo, hi);                   // second read of the tile, for the packing below
+            nlo = lo; nhi = hi;
         }
-        load_syms(c0, lo, hi);                       // second read of the tile (L2), for the packing below
-        nlo = lo; nhi = hi;
         __syncthreads();
         uint32_t tile_units = 0;
 #pragma unroll
@@ -505,14 +515,20 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
             u_img += uq;
             left -= uq;
         };
+        if (short_codes) {
+#pragma unroll
+            for (int q = 0; q < kTileMax; ++q)
+                if (q < (int)nq) pack_chunk(q, sv[q][0], sv[q][1], r.pos[q]);     // uniform
+        } else {
 #pragma unroll 1
-        for (int q = 0; q < kTileMax; ++q) {
-            if (q < (int)nq) {                       // uniform
-                if (q + 1 < (int)nq) load_syms(c0 + q + 1, nlo, nhi);
-                pack_chunk(q, lo, hi, r.pos[0]);
-                lo = nlo; hi = nhi;
+            for (int q = 0; q < kTileMax; ++q) {
+                if (q < (int)nq) {
+                    if (q + 1 < (int)nq) load_syms(c0 + q + 1, nlo, nhi);
+                    pack_chunk(q, lo, hi, r.pos[0]);
+                    lo = nlo; hi = nhi;
+                }
+                r.rotate();
             }
-            r.rotate();
         }
         PHASE(4)
         __syncthreads();                             // image complete
@@ -651,9 +667,9 @@ void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st)
     launch_codebook(a, prof, st);
     const uint32_t ntiles = (nchunks + a.tile_chunks - 1) / a.tile_chunks;
     // every workgroup costs a ticket, a look-back over the tiles in flight and a code table load:
-    // about one workgroup per 16 chunks, between one and four per CU
+    // about one workgroup per 16 chunks, between one and three (what fits) per CU
     uint32_t egrid = nchunks / 16;
-    egrid = egrid < 256u ? 256u : egrid > 1024u ? 1024u : egrid;
+    egrid = egrid < 256u ? 256u : egrid > 768u ? 768u : egrid;
     egrid = egrid < ntiles ? egrid : ntiles;
     launch(prof, kKEncode, k_encode, dim3(egrid), dim3(kThreads), st, a);
     launch(prof, kKOutliers, k_outliers, dim3(nchunks), dim3(kThreads), st, a);
