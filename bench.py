@@ -45,6 +45,19 @@ KERNEL_BYTES = {
 }
 
 
+# HBM bytes per element actually moved, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by a
+# plain copy of known size (profiles/hbm_traffic_cfg5_resnet18_stream.txt has the commands and the
+# readings).  Counters cannot be read from inside this process, so the figures are only reported
+# for the configuration they were measured on.
+MEASURED_TRAFFIC = {
+    ("cfg5_resnet18_stream", 32, 1e-2): {
+        "k_quant_lorenzo_split_hist": 4.0121 + 2.0323,
+        "k_encode": 2.0321 + 0.7233,
+        "k_decode_fused": 0.7935 + 4.0075,
+    },
+}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -178,8 +191,12 @@ def main() -> int:
     if bytes_fn is not None:
         alg_bytes_step = bytes_fn(cbar) * total                 # over all launches of one step
         achieved = alg_bytes_step / (kern[dom]["ms_per_step"] * 1e-3) / 1e9
+        per_elem = MEASURED_TRAFFIC.get((wl.name, args.sub, eb), {}).get(dom)
+        # measured HBM bytes per launch (average over the launches of a step), like `achieved`
+        traffic = round(per_elem * total / kern[dom]["launches_per_step"]) if per_elem else None
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                    "alg_bytes_per_launch": round(alg_bytes_step / kern[dom]["launches_per_step"]),
                     "alg_bytes_per_elem": round(bytes_fn(cbar), 4),
                     "avg_launch_us": round(kern[dom]["avg_us"], 2),
                     "launches_per_step": kern[dom]["launches_per_step"]}
