@@ -201,6 +201,17 @@ def main() -> int:
                     "avg_launch_us": round(kern[dom]["avg_us"], 2),
                     "launches_per_step": kern[dom]["launches_per_step"]}
 
+    # what a plain device copy of the largest tensor reaches on this machine (bytes read + written)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    outs[0].copy_(xs[0])
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(5):
+        outs[0].copy_(xs[0])
+    ev[1].record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * 4.0 * numels[0] / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+
     value = 2 * 4.0 * total / (ms_per_step * 1e-3) / 1e9
     alg_roundtrip = (12.0 + 2 * cbar) * total                  # 8 + cbar compress, 4 + cbar decompress
     result = {
@@ -217,6 +228,7 @@ def main() -> int:
         "compress_GBps": round(4.0 * total / (tc * 1e-3) / 1e9, 2),
         "decompress_GBps": round(4.0 * total / (td * 1e-3) / 1e9, 2),
         "hbm_frac_algorithmic": round(alg_roundtrip / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "copy_ceiling_GBps": round(copy_gbps, 1),
         "max_abs_err": worst,
         "kernels": {k: {kk: round(vv, 3) for kk, vv in v.items()} for k, v in kern.items()},
         "roofline": roofline,

@@ -1,0 +1,87 @@
+"""Saved-tensor hooks (phase 4 of the framework, Section 4.4): the arena on the CPU, the hooks on the GPU."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2011_09017_amd.autograd import Arena
+
+
+def test_arena_is_a_stack_that_tolerates_out_of_order_release():
+    a = Arena(4096)
+    x = a.alloc(100)
+    a.shrink_last(100)
+    y = a.alloc(300)
+    a.shrink_last(10)
+    z = a.alloc(256)
+    a.shrink_last(256)
+    assert (x, y, z) == (0, 256, 512) and a.top == 768 and a.peak == 768 and a.peak_reserved == 768
+    a.free(y)                       # a hole below the top: space stays taken
+    assert a.top == 768 and a.live_bytes == 512
+    a.free(z)                       # top and the hole come back together
+    assert a.top == 256
+    a.free(x)
+    assert a.top == 0 and a.live_bytes == 0 and a.peak == 768
+    with pytest.raises(MemoryError):
+        a.alloc(5000)
+    with pytest.raises(KeyError):
+        a.free(123)
+
+
+@pytest.mark.gpu
+def test_hooks_compress_conv_inputs_and_restore_the_oracle_reconstruction(orc):
+    """A small conv stack: what the backward pass receives is, bit for bit, the oracle's
+    reconstruction of what the forward pass saved; the arena is empty afterwards."""
+    from paper_2011_09017_amd.autograd import ActivationCompressor
+    torch.manual_seed(2011_09017)
+    dev = torch.device("cuda", 0)
+    model = torch.nn.Sequential(
+        torch.nn.Conv2d(8, 16, 3, padding=1), torch.nn.ReLU(),
+        torch.nn.Conv2d(16, 16, 3, padding=1), torch.nn.ReLU(),
+        torch.nn.Conv2d(16, 4, 3, padding=1)).to(dev)
+    x = torch.randn(4, 8, 32, 32, device=dev)
+    eb = 1e-2
+
+    def run(comp):
+        model.zero_grad()
+        if comp is None:
+            loss = model(x).square().mean()
+        else:
+            with comp.hooks():
+                loss = model(x).square().mean()
+        loss.backward()
+        return [p.grad.clone() for p in model.parameters()]
+
+    ref = run(None)
+    comp = ActivationCompressor(eb, arena_bytes=8 << 20, max_numel=1 << 20, min_numel=1 << 12)
+    comp.skip_parameters(model.parameters())
+    seen = []
+    comp.on_unpack = lambda p, t: seen.append((p, t.clone()))
+    saved = []
+    orig_pack = comp.pack
+
+    def spy(t):
+        r = orig_pack(t)
+        if not isinstance(r, torch.Tensor):
+            saved.append((r, t.detach().clone()))
+        return r
+    comp.pack = spy
+    got = run(comp)
+
+    assert comp.stats["packed"] >= 3                       # the input of every convolution
+    assert comp.arena.top == 0 and comp.arena.live_bytes == 0
+    assert comp.stats["container_bytes"] < comp.stats["raw_bytes"] // 2
+    assert 0 < comp.arena.peak <= comp.stats["container_bytes"] + 256 * comp.stats["packed"]
+    originals = {id(p): t for p, t in saved}
+    assert len(seen) == len(originals)
+    for p, restored in seen:
+        xh = originals[id(p)].cpu().numpy()
+        rc, buf, size, _ = orc.compress(xh, eb, orc.Config(sub=32))
+        assert rc == 0 and size == p.size
+        rc, y = orc.decompress(buf, xh.shape, eb, orc.Config(sub=32))
+        assert rc == 0
+        assert np.array_equal(restored.cpu().numpy().view(np.uint32), y.view(np.uint32))
+        assert np.abs(y.astype(np.float64) - xh.astype(np.float64)).max() <= float(np.float32(eb))
+    # gradients: finite, and close to those of the uncompressed run (activation error <= eb)
+    for g, r in zip(got, ref):
+        assert torch.isfinite(g).all()
+        assert (g - r).abs().max() <= 0.05 * r.abs().max() + 1e-6
