@@ -82,6 +82,7 @@ def lib() -> C.CDLL:
         L.orc_decompress.argtypes = [vp, sz, vp, f32, vp, vp]; L.orc_decompress.restype = C.c_int
         L.orc_decode_deltas.argtypes = [vp, sz, vp, vp, vp]; L.orc_decode_deltas.restype = C.c_int
         L.orc_dequant.argtypes = [vp, sz, f32, vp]; L.orc_dequant.restype = None
+        L.orc_estimate_eb.argtypes = [vp, sz, vp, sz, sz, vp, sz, vp, vp, vp]; L.orc_estimate_eb.restype = C.c_int
         _lib = L
     return _lib
 
@@ -266,3 +267,18 @@ def parse_header(buf: np.ndarray) -> dict:
         else:
             out[k] = int(b[o:o + 4].view("<u4")[0])
     return out
+
+
+def estimate_eb(act: np.ndarray, loss: np.ndarray, mom: np.ndarray, sigma_frac=0.01, a=0.32, eb_min=1e-6, eb_max=1.0):
+    """Sections 4.1-4.3: loss has shape (batch_n, ...).  Returns (rc, eb as float32, (R, Lbar, Mavg))."""
+    act = np.ascontiguousarray(act, dtype=np.float32)
+    loss = np.ascontiguousarray(loss, dtype=np.float32)
+    mom = np.ascontiguousarray(mom, dtype=np.float32)
+    batch_n = loss.shape[0]
+    per_sample = loss.size // batch_n if batch_n else 0
+    cfg = np.array([sigma_frac, a, eb_min, eb_max], dtype=np.float32)
+    eb = np.zeros(1, dtype=np.float32)
+    stats = np.zeros(3, dtype=np.float64)
+    rc = lib().orc_estimate_eb(_p(act), act.size, _p(loss), batch_n, per_sample, _p(mom), mom.size, _p(cfg), _p(eb),
+                               _p(stats))
+    return rc, eb[0], tuple(stats)

@@ -742,3 +742,73 @@ void orc_dequant(const int32_t *q, size_t n, float s, float *xout)
         xout[i] = (q[i] == 0) ? 0.0f : v;
     }
 }
+
+/* ------------------------------------------------------------------------
+ * Error-bound estimator of the adaptive framework (Sections 4.1-4.3).
+ *
+ * Collected every W iterations (Section 4.1):
+ *   R      fraction of non-zero elements of the activation tensor (Eq. 9: the
+ *          predicted sigma shrinks by sqrt(R) because zeros carry no error);
+ *   Lbar   "average value of the current layer's loss" (Eq. 5).  Reading taken
+ *          here: the loss arrives as batch_n samples of per_sample values each;
+ *          Lbar is the mean over the samples of each sample's largest |value|;
+ *   Mavg   "average value of the momentum" (Eq. 7).  Reading: mean of |m|.
+ * Then (Eq. 7, Eq. 8 with the sqrt(R) of Eq. 9, a = 0.32 in Section 5.1):
+ *   sigma = sigma_frac * Mavg,   eb = sigma / (a * Lbar * sqrt(batch_n * R)).
+ * All arithmetic in fp64; the result is rounded once to fp32 and clamped to
+ * [eb_min, eb_max].  When the denominator is not a positive finite number
+ * (all-zero activation, zero loss, NaN anywhere) or Mavg is not finite, the
+ * tightest bound eb_min is returned together with ORC_W_RANGE.
+ * stats[0..2] = R, Lbar, Mavg.
+ *
+ * Pins (tests/test_oracle_controller.py): exact closed forms (all parameters
+ * powers of two), the sqrt(2) law of Section 3.2 for a doubled batch, the
+ * sqrt(R) law of Eq. 9, independent numpy statistics, clamping and the
+ * degenerate cases.  The two readings above (Lbar, Mavg) are conventions:
+ * apart from those pins they are "parity unpinned".
+ * ------------------------------------------------------------------------ */
+typedef struct {
+    float sigma_frac;   /* 0.01 in the paper */
+    float a;            /* 0.32 in the paper */
+    float eb_min, eb_max;
+} orc_controller_config;
+
+int orc_estimate_eb(const float *act, size_t act_numel, const float *loss, size_t batch_n, size_t per_sample,
+                    const float *mom, size_t mom_numel, const orc_controller_config *cfg, float *eb_out,
+                    double stats[3])
+{
+    if (!cfg || !eb_out || !act || !loss || !mom) return ORC_E_ARG;
+    if (act_numel == 0 || batch_n == 0 || per_sample == 0 || mom_numel == 0) return ORC_E_ARG;
+    if (!(cfg->eb_min > 0.0f) || !(cfg->eb_max >= cfg->eb_min) || !(cfg->sigma_frac > 0.0f) || !(cfg->a > 0.0f))
+        return ORC_E_ARG;
+
+    size_t nonzero = 0;
+    for (size_t i = 0; i < act_numel; ++i) nonzero += (act[i] != 0.0f) ? 1u : 0u;      /* NaN counts as non-zero */
+    const double R = (double)nonzero / (double)act_numel;
+
+    double lsum = 0.0;
+    for (size_t n = 0; n < batch_n; ++n) {
+        double m = 0.0;
+        for (size_t k = 0; k < per_sample; ++k) {
+            const double v = fabs((double)loss[n * per_sample + k]);
+            if (!(v <= m)) m = v;                                   /* a NaN sticks */
+        }
+        lsum += m;
+    }
+    const double Lbar = lsum / (double)batch_n;
+
+    double msum = 0.0;
+    for (size_t i = 0; i < mom_numel; ++i) msum += fabs((double)mom[i]);
+    const double Mavg = msum / (double)mom_numel;
+
+    if (stats) { stats[0] = R; stats[1] = Lbar; stats[2] = Mavg; }
+    const double sigma = (double)cfg->sigma_frac * Mavg;
+    const double denom = (double)cfg->a * Lbar * sqrt((double)batch_n * R);
+    if (!(denom > 0.0) || !isfinite(denom) || !isfinite(sigma)) { *eb_out = cfg->eb_min; return ORC_W_RANGE; }
+    float eb = (float)(sigma / denom);
+    if (!(eb >= cfg->eb_min)) eb = cfg->eb_min;
+    if (eb > cfg->eb_max) eb = cfg->eb_max;
+    *eb_out = eb;
+    return ORC_OK;
+}
+
