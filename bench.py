@@ -212,6 +212,19 @@ def main() -> int:
     torch.cuda.synchronize()
     copy_gbps = 5 * 2 * 4.0 * numels[0] / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
 
+    # the error-bound estimator (Sections 4.1-4.3; it runs every W = 1000 iterations, so it is not
+    # part of a step): one streaming pass over an activation, a loss of the same shape and a momentum
+    ctl_ctx = ctxs[0]
+    mom = xs[-1].reshape(-1)[: 512 * 512 * 9].contiguous()
+    ctl_ctx.estimate_eb(xs[0], outs[0], mom)
+    ctl_ctx.profile(True)
+    for _ in range(5):
+        rc_ctl, eb_ctl, st_ctl = ctl_ctx.estimate_eb(xs[0], outs[0], mom)
+    ctl_ms, ctl_n = ctl_ctx.profile_read()["k_controller_stats"]
+    ctl_ctx.profile(False)
+    ctl_bytes = 4.0 * (2 * numels[0] + mom.numel())
+    ctl_gbps = ctl_bytes / (ctl_ms / ctl_n * 1e-3) / 1e9
+
     value = 2 * 4.0 * total / (ms_per_step * 1e-3) / 1e9
     alg_roundtrip = (12.0 + 2 * cbar) * total                  # 8 + cbar compress, 4 + cbar decompress
     result = {
@@ -229,6 +242,10 @@ def main() -> int:
         "decompress_GBps": round(4.0 * total / (td * 1e-3) / 1e9, 2),
         "hbm_frac_algorithmic": round(alg_roundtrip / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "copy_ceiling_GBps": round(copy_gbps, 1),
+        "controller": {"kernel": "k_controller_stats", "bound": "hbm", "achieved": round(ctl_gbps, 1),
+                       "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ctl_gbps / HBM_PEAK_GBPS, 4),
+                       "avg_launch_us": round(1e3 * ctl_ms / ctl_n, 2), "alg_bytes_per_launch": int(ctl_bytes),
+                       "eb": eb_ctl, "R": st_ctl[0]},
         "max_abs_err": worst,
         "kernels": {k: {kk: round(vv, 3) for kk, vv in v.items()} for k, v in kern.items()},
         "roofline": roofline,

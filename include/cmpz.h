@@ -150,6 +150,35 @@ int cmp_profile(cmp_ctx *ctx, int enable);
 int cmp_profile_read(cmp_ctx *ctx, void *stream, int cap, const char **h_names,
                      double *h_total_ms, uint64_t *h_launches);
 
+/* Error-bound estimate of the adaptive framework (Sections 4.1-4.3), to be called every W
+ * iterations for a convolutional layer.  One kernel reduces three device arrays:
+ *   d_act   the layer's activation tensor, act_numel values: R = fraction of non-zero elements
+ *           (Eq. 9);
+ *   d_loss  the loss arriving at the layer in the backward pass, batch_n samples of per_sample
+ *           consecutive values: Lbar = mean over the samples of each sample's largest |value|
+ *           (the "average loss" of Eq. 5, as read by this library);
+ *   d_mom   the momentum of the layer's weights, mom_numel values: Mavg = mean of |m| (Eq. 7);
+ * and evaluates, in fp64 on the device, sigma = sigma_frac * Mavg (Eq. 7) and
+ * eb = sigma / (a * Lbar * sqrt(batch_n * R)) (Eq. 8 with the sqrt(R) of Eq. 9), rounded once to
+ * fp32 and clamped to [eb_min, eb_max].  Waits for `stream`, then stores the bound in *h_eb and,
+ * if h_stats != NULL, R, Lbar, Mavg in h_stats[0..2].  The pointers must be 16-byte aligned, the
+ * arrays non-empty, each shorter than 2^32 values, batch_n <= 65536.
+ * Returns CMP_W_RANGE and eb_min when there is nothing to estimate from (no non-zero activation,
+ * zero loss, NaN or infinity in a statistic); CMP_E_ARG on bad arguments. */
+typedef struct {
+    float sigma_frac;   /* acceptable gradient error as a fraction of the momentum: 0.01 (Eq. 7) */
+    float a;            /* empirical coefficient of Eq. 5: 0.32 (Section 5.1)                   */
+    float eb_min;       /* > 0                                                                   */
+    float eb_max;       /* >= eb_min                                                             */
+} cmp_controller_config;
+
+/* Defaults: sigma_frac 0.01, a 0.32, eb_min 1e-6, eb_max 1. */
+void cmp_default_controller_config(cmp_controller_config *cfg);
+
+int cmp_estimate_eb(cmp_ctx *ctx, const float *d_act, uint64_t act_numel, const float *d_loss, uint64_t batch_n,
+                    uint64_t per_sample, const float *d_mom, uint64_t mom_numel, const cmp_controller_config *cfg,
+                    float *h_eb, double *h_stats, void *stream);
+
 const char *cmp_strerror(int code);
 
 #ifdef __cplusplus

@@ -789,11 +789,13 @@ int orc_estimate_eb(const float *act, size_t act_numel, const float *loss, size_
     double lsum = 0.0;
     for (size_t n = 0; n < batch_n; ++n) {
         double m = 0.0;
+        int nan_seen = 0;
         for (size_t k = 0; k < per_sample; ++k) {
             const double v = fabs((double)loss[n * per_sample + k]);
-            if (!(v <= m)) m = v;                                   /* a NaN sticks */
+            if (isnan(v)) nan_seen = 1;
+            else if (v > m) m = v;
         }
-        lsum += m;
+        lsum += nan_seen ? (double)NAN : m;                         /* a NaN anywhere in the sample sticks */
     }
     const double Lbar = lsum / (double)batch_n;
 

@@ -21,7 +21,11 @@ CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES, CMP_STAG
 
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
            "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",
-           "cmp_profile", "cmp_profile_read"]
+           "cmp_profile", "cmp_profile_read", "cmp_default_controller_config", "cmp_estimate_eb"]
+
+
+class cmp_controller_config(C.Structure):
+    _fields_ = [("sigma_frac", C.c_float), ("a", C.c_float), ("eb_min", C.c_float), ("eb_max", C.c_float)]
 
 
 class cmp_config(C.Structure):
@@ -52,6 +56,9 @@ def lib() -> C.CDLL:
         L.cmp_last_status.argtypes = [vp, vp]; L.cmp_last_status.restype = i32
         L.cmp_debug_stage.argtypes = [vp, i32, vp, vp]; L.cmp_debug_stage.restype = i32
         L.cmp_strerror.argtypes = [i32]; L.cmp_strerror.restype = C.c_char_p
+        L.cmp_default_controller_config.argtypes = [vp]; L.cmp_default_controller_config.restype = None
+        L.cmp_estimate_eb.argtypes = [vp, vp, C.c_uint64, vp, C.c_uint64, C.c_uint64, vp, C.c_uint64, vp, vp, vp, vp]
+        L.cmp_estimate_eb.restype = i32
         L.cmp_profile.argtypes = [vp, i32]; L.cmp_profile.restype = i32
         L.cmp_profile_read.argtypes = [vp, vp, i32, vp, vp, vp]; L.cmp_profile_read.restype = i32
         _lib = L
@@ -129,6 +136,16 @@ def cmp_profile_read(ctx, stream: int, cap: int = 32):
     return n, {names[k].decode(): (float(ms[k]), int(launches[k])) for k in range(min(n, cap))}
 
 
+def cmp_estimate_eb(ctx, d_act: int, act_numel: int, d_loss: int, batch_n: int, per_sample: int, d_mom: int,
+                    mom_numel: int, cfg: "cmp_controller_config | None", stream: int):
+    """Returns (rc, eb, (R, Lbar, Mavg))."""
+    eb = C.c_float(0.0)
+    stats = (C.c_double * 3)()
+    rc = lib().cmp_estimate_eb(ctx, d_act, act_numel, d_loss, batch_n, per_sample, d_mom, mom_numel,
+                               C.addressof(cfg) if cfg is not None else None, C.addressof(eb), C.addressof(stats), stream)
+    return rc, float(eb.value), (stats[0], stats[1], stats[2])
+
+
 def cmp_strerror(code: int) -> str:
     return lib().cmp_strerror(code).decode()
 
@@ -188,6 +205,20 @@ class Context:
         if rc != CMP_OK:
             raise CmpError(rc, "cmp_decompress")
         return out
+
+    def estimate_eb(self, act: torch.Tensor, loss: torch.Tensor, mom: torch.Tensor, sigma_frac=0.01, a=0.32,
+                    eb_min=1e-6, eb_max=1.0):
+        """Sections 4.1-4.3: loss has shape (batch_n, ...).  Returns (rc, eb, (R, Lbar, Mavg))."""
+        for t in (act, loss, mom):
+            assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+        cfg = cmp_controller_config(sigma_frac, a, eb_min, eb_max)
+        batch_n = loss.shape[0]
+        rc, eb, stats = cmp_estimate_eb(self._h, act.data_ptr(), act.numel(), loss.data_ptr(), batch_n,
+                                        loss.numel() // max(batch_n, 1), mom.data_ptr(), mom.numel(), cfg,
+                                        self._stream())
+        if rc < 0:
+            raise CmpError(rc, "cmp_estimate_eb")
+        return rc, eb, stats
 
     def last_status(self, stream: int | None = None) -> int:
         return cmp_last_status(self._h, self._stream() if stream is None else stream)

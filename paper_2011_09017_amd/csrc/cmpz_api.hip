@@ -12,7 +12,7 @@ namespace cmpz {
 const char *const kKernelNames[kKernelCount] = {
     "k_quant_lorenzo_split_hist", "k_codebook", "k_chunk_bits", "k_scan_header", "k_encode", "k_outliers",
     "k_empty_container", "k_decode_tables", "k_decode", "k_patch_outliers", "k_row_scan",
-    "k_col_scan_dequant", "k_decode_fused"};
+    "k_col_scan_dequant", "k_decode_fused", "k_controller_stats"};
 }  // namespace cmpz
 
 using namespace cmpz;
@@ -28,6 +28,8 @@ struct cmp_ctx {
     uint8_t   *d_lens;
     uint64_t  *d_codes;
     void      *d_tables;
+    ControllerScratch *d_ctl;
+    ControllerResult  *d_ctl_result;
     uint64_t   last_numel;
     Profiler   prof;
 };
@@ -150,6 +152,8 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     const uint64_t o_lens = carve(kMaxSym);
     const uint64_t o_codes = carve(8 * kMaxSym);
     const uint64_t o_tables = carve(decode_tables_bytes());
+    const uint64_t o_ctl = carve(sizeof(ControllerScratch));
+    const uint64_t o_ctl_result = carve(sizeof(ControllerResult));
     if (hipMalloc(reinterpret_cast<void **>(&ctx->d_base), off) != hipSuccess) { delete ctx; return CMP_E_HIP; }
     // only the small control words need a defined start value; the symbol scratch does not
     if (hipMemset(ctx->d_base + o_hist, 0, off - o_hist) != hipSuccess) {
@@ -165,6 +169,8 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     ctx->d_lens = ctx->d_base + o_lens;
     ctx->d_codes = reinterpret_cast<uint64_t *>(ctx->d_base + o_codes);
     ctx->d_tables = ctx->d_base + o_tables;
+    ctx->d_ctl = reinterpret_cast<ControllerScratch *>(ctx->d_base + o_ctl);
+    ctx->d_ctl_result = reinterpret_cast<ControllerResult *>(ctx->d_base + o_ctl_result);
     *out = ctx;
     return CMP_OK;
 }
@@ -347,6 +353,45 @@ int cmp_profile_read(cmp_ctx *ctx, void *stream, int cap, const char **names, do
         ++n;
     }
     return n;
+}
+
+void cmp_default_controller_config(cmp_controller_config *cfg)
+{
+    if (!cfg) return;
+    cfg->sigma_frac = 0.01f; cfg->a = 0.32f; cfg->eb_min = 1e-6f; cfg->eb_max = 1.0f;
+}
+
+int cmp_estimate_eb(cmp_ctx *ctx, const float *d_act, uint64_t act_numel, const float *d_loss, uint64_t batch_n,
+                    uint64_t per_sample, const float *d_mom, uint64_t mom_numel, const cmp_controller_config *cfg,
+                    float *h_eb, double *h_stats, void *stream)
+{
+    if (!ctx || !d_act || !d_loss || !d_mom || !h_eb) return CMP_E_ARG;
+    cmp_controller_config c;
+    if (cfg) c = *cfg; else cmp_default_controller_config(&c);
+    if (!(c.eb_min > 0.0f) || !(c.eb_max >= c.eb_min) || !(c.sigma_frac > 0.0f) || !(c.a > 0.0f)) return CMP_E_ARG;
+    if (act_numel == 0 || batch_n == 0 || per_sample == 0 || mom_numel == 0) return CMP_E_ARG;
+    if (batch_n > kMaxBatch || per_sample >= (1ull << 32) || batch_n * per_sample >= (1ull << 32)) return CMP_E_ARG;
+    if (act_numel >= (1ull << 32) || mom_numel >= (1ull << 32)) return CMP_E_ARG;
+    if ((reinterpret_cast<uintptr_t>(d_act) | reinterpret_cast<uintptr_t>(d_loss) | reinterpret_cast<uintptr_t>(d_mom)) & 15)
+        return CMP_E_ARG;
+
+    ControllerArgs a;
+    a.act = d_act; a.loss = d_loss; a.mom = d_mom;
+    a.n_act = (uint32_t)act_numel; a.n_loss = (uint32_t)(batch_n * per_sample); a.n_mom = (uint32_t)mom_numel;
+    a.batch_n = (uint32_t)batch_n; a.per_sample = (uint32_t)per_sample;
+    a.sigma_frac = c.sigma_frac; a.a = c.a; a.eb_min = c.eb_min; a.eb_max = c.eb_max;
+    a.scratch = ctx->d_ctl; a.result = ctx->d_ctl_result;
+
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    launch_controller(a, &ctx->prof, st);
+    ControllerResult res;
+    if (hipMemcpyAsync(&res, ctx->d_ctl_result, sizeof(res), hipMemcpyDeviceToHost, st) != hipSuccess) return CMP_E_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return CMP_E_HIP;
+    *h_eb = res.eb;
+    if (h_stats) { h_stats[0] = res.stats[0]; h_stats[1] = res.stats[1]; h_stats[2] = res.stats[2]; }
+    return res.rc ? CMP_W_RANGE : CMP_OK;
 }
 
 const char *cmp_strerror(int code)

@@ -196,7 +196,8 @@ __device__ __forceinline__ uint32_t rank_within_length(uint32_t L, uint32_t (*wa
 // Kernel identifiers for the optional per-kernel timing (cmp_profile).
 enum KernelId : int {
     kKQuantLorenzoHist = 0, kKCodebook, kKChunkBits, kKScanHeader, kKEncode, kKOutliers, kKEmpty,
-    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKernelCount
+    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKControllerStats,
+    kKernelCount
 };
 extern const char *const kKernelNames[kKernelCount];
 
@@ -234,5 +235,28 @@ bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st);
 size_t decode_tables_bytes();
 void launch_decompress(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st);
 bool launch_decode_fused(const DecompressArgs &a, Profiler *prof, hipStream_t st);
+
+// Error-bound estimator: device scratch (zero between calls) and result record.
+constexpr uint32_t kMaxBatch = 65536;
+struct ControllerScratch {
+    unsigned long long nonzero;     // activation elements != 0
+    double             msum;        // sum of |momentum|
+    uint32_t           done;        // workgroups finished
+    uint32_t           pad;
+    uint32_t           maxbits[kMaxBatch];   // per sample: bit pattern of the largest |loss| (a NaN pattern wins)
+};
+struct ControllerResult {
+    float    eb;
+    int32_t  rc;                    // 0 or 1 (nothing to estimate from)
+    double   stats[3];              // R, Lbar, Mavg
+};
+struct ControllerArgs {
+    const float *act, *loss, *mom;
+    uint32_t n_act, n_loss, n_mom, batch_n, per_sample;
+    float sigma_frac, a, eb_min, eb_max;
+    ControllerScratch *scratch;
+    ControllerResult  *result;
+};
+void launch_controller(const ControllerArgs &a, Profiler *prof, hipStream_t st);
 
 }  // namespace cmpz

@@ -74,7 +74,9 @@ def test_clamping_and_degenerate_inputs(orc):
     rc, eb, _ = orc.estimate_eb(one, loss, 1e-9 * mom, eb_min=1e-4)
     assert rc == 0 and eb == np.float32(1e-4)
     # nothing to estimate from: the tightest bound and a warning
-    for a_, l_, m_ in ((0 * one, loss, mom), (one, 0 * loss, mom), (one, loss * np.nan, mom),
+    one_nan = loss.copy()
+    one_nan[1, 1] = np.nan                              # a single NaN, followed by ordinary values
+    for a_, l_, m_ in ((0 * one, loss, mom), (one, 0 * loss, mom), (one, loss * np.nan, mom), (one, one_nan, mom),
                        (one, loss, mom * np.inf)):
         rc, eb, _ = orc.estimate_eb(a_, l_, m_, eb_min=1e-4)
         assert rc == 1 and eb == np.float32(1e-4)
