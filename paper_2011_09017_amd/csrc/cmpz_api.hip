@@ -10,7 +10,7 @@
 
 namespace cmpz {
 const char *const kKernelNames[kKernelCount] = {
-    "k_quant_lorenzo_split_hist", "k_codebook", "k_chunk_bits", "k_scan_header", "k_encode", "k_outliers",
+    "k_quant_lorenzo_split_hist", "k_codebook", "k_encode", "k_outliers",
     "k_empty_container", "k_decode_tables", "k_decode", "k_patch_outliers", "k_row_scan",
     "k_col_scan_dequant", "k_decode_fused", "k_controller_stats"};
 }  // namespace cmpz

@@ -195,7 +195,7 @@ __device__ __forceinline__ uint32_t rank_within_length(uint32_t L, uint32_t (*wa
 
 // Kernel identifiers for the optional per-kernel timing (cmp_profile).
 enum KernelId : int {
-    kKQuantLorenzoHist = 0, kKCodebook, kKChunkBits, kKScanHeader, kKEncode, kKOutliers, kKEmpty,
+    kKQuantLorenzoHist = 0, kKCodebook, kKEncode, kKOutliers, kKEmpty,
     kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKControllerStats,
     kKernelCount
 };
