@@ -67,6 +67,11 @@ def main() -> int:
     ap.add_argument("--eb", type=float, default=None)
     ap.add_argument("--sub", type=int, default=32, help="codes per sub-block (decode parallelism vs. 16 bits of metadata each)")
     ap.add_argument("--streams", type=int, default=3, help="contexts/streams the tensors are dealt over, round robin")
+    ap.add_argument("--contexts", type=int, default=6, help="compress contexts (tensors in flight) of the pipelined schedule")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="all first sweeps (cmp_compress_begin) on one stream and the codebook / second sweep "
+                         "(cmp_compress_finish) of alternate tensors on two others, instead of whole cmp_compress "
+                         "calls dealt round robin over the streams (measured: no faster, 3.55 against 3.45 ms)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of tensor 0 (numel*4 bytes read and written): "
@@ -93,7 +98,11 @@ def main() -> int:
     numels = [x.numel() for x in xs]
     total = sum(numels)
     S = max(1, min(args.streams, len(xs)))
-    ctxs = [binding.Context(sub=args.sub, max_numel=max(numels[k::S])) for k in range(S)]
+    K = max(S, args.contexts) if args.pipeline and S >= 3 else S       # compress contexts (tensors in flight)
+    ctxs = [binding.Context(sub=args.sub, max_numel=max(numels[k::K])) for k in range(K)]
+    # decompression gets contexts of its own: calls of one context must not overlap, and in the
+    # pipelined schedule a context's next compress may start while the last decompress still runs
+    dctxs = [binding.Context(sub=args.sub, max_numel=max(numels[k::S])) for k in range(S)]
     bounds = [ctxs[0].bound(x.shape) for x in xs]
     arena = [torch.empty(b, dtype=torch.uint8, device=dev) for b in bounds]
     outs = [torch.empty_like(x) for x in xs]
@@ -102,19 +111,51 @@ def main() -> int:
     streams = [t.cuda_stream for t in tstreams]
     order = list(range(len(xs)))
 
+    pipeline = args.pipeline and S >= 3
+    # pipelined forward pass: stream 0 runs every first sweep (cmp_compress_begin), streams 1 and 2
+    # take the codebook and second sweep (cmp_compress_finish) of alternate tensors, so that the
+    # one-workgroup codebook kernel of a tensor always has the first sweep of the next one beside it
+    fin_ev = [None] * len(xs)                       # container i complete
+    dec_ev = [None] * len(xs)                       # container i consumed by the last decompress
+    ctx_free = [None] * K                           # last finish issued on context k
+
     def compress_all():
+        if not pipeline:
+            for i in order:
+                x, buf = xs[i], arena[i]
+                rc, _ = binding.cmp_compress(ctxs[i % K]._h, x.data_ptr(), x.shape, eb, buf.data_ptr(), buf.numel(),
+                                             False, streams[i % S])
+                assert rc == 0, binding.cmp_strerror(rc)
+            return
         for i in order:
-            x, buf = xs[i], arena[i]
-            rc, _ = binding.cmp_compress(ctxs[i % S]._h, x.data_ptr(), x.shape, eb, buf.data_ptr(), buf.numel(),
-                                         False, streams[i % S])
+            k = i % K
+            side = 1 + (i & 1)
+            if ctx_free[k] is not None:
+                tstreams[0].wait_event(ctx_free[k])
+            rc = binding.cmp_compress_begin(ctxs[k]._h, xs[i].data_ptr(), xs[i].shape, eb, streams[0])
             assert rc == 0, binding.cmp_strerror(rc)
+            began = torch.cuda.Event()
+            began.record(tstreams[0])
+            tstreams[side].wait_event(began)
+            if dec_ev[i] is not None:
+                tstreams[side].wait_event(dec_ev[i])
+            rc, _ = binding.cmp_compress_finish(ctxs[k]._h, arena[i].data_ptr(), arena[i].numel(), False, streams[side])
+            assert rc == 0, binding.cmp_strerror(rc)
+            fin_ev[i] = torch.cuda.Event()
+            fin_ev[i].record(tstreams[side])
+            ctx_free[k] = fin_ev[i]
 
     def decompress_all():
         for i in reversed(order):
             x = xs[i]
-            rc = binding.cmp_decompress(ctxs[i % S]._h, arena[i].data_ptr(), bounds[i], x.shape, eb,
+            if pipeline:
+                tstreams[i % S].wait_event(fin_ev[i])
+            rc = binding.cmp_decompress(dctxs[i % S]._h, arena[i].data_ptr(), bounds[i], x.shape, eb,
                                         outs[i].data_ptr(), streams[i % S])
             assert rc == 0, binding.cmp_strerror(rc)
+            if pipeline:
+                dec_ev[i] = torch.cuda.Event()
+                dec_ev[i].record(tstreams[i % S])
 
     def step():
         compress_all()
@@ -126,8 +167,8 @@ def main() -> int:
     if args.calib_copy:
         outs[0].copy_(xs[0])
         torch.cuda.synchronize()
-    for k in range(S):
-        st = ctxs[k].last_status(streams[k])
+    for c in ctxs + dctxs:
+        st = c.last_status(streams[0])
         assert st == 0, binding.cmp_strerror(st)
     sizes = []
     for buf in arena:
@@ -168,18 +209,18 @@ def main() -> int:
         c.profile(True)
     for _ in range(args.steps):
         for i in order:
-            rc, _ = binding.cmp_compress(ctxs[i % S]._h, xs[i].data_ptr(), xs[i].shape, eb, arena[i].data_ptr(),
+            rc, _ = binding.cmp_compress(ctxs[i % K]._h, xs[i].data_ptr(), xs[i].shape, eb, arena[i].data_ptr(),
                                          arena[i].numel(), False, streams[i % S])
             assert rc == 0, binding.cmp_strerror(rc)
             torch.cuda.synchronize()
         for i in reversed(order):
-            rc = binding.cmp_decompress(ctxs[i % S]._h, arena[i].data_ptr(), bounds[i], xs[i].shape, eb,
+            rc = binding.cmp_decompress(ctxs[i % K]._h, arena[i].data_ptr(), bounds[i], xs[i].shape, eb,
                                         outs[i].data_ptr(), streams[i % S])
             assert rc == 0, binding.cmp_strerror(rc)
             torch.cuda.synchronize()
     kern = {}
     for k, c in enumerate(ctxs):
-        for name, (ms, launches) in c.profile_read(streams[k]).items():
+        for name, (ms, launches) in c.profile_read(streams[0]).items():
             e = kern.setdefault(name, {"ms": 0.0, "launches": 0})
             e["ms"] += ms; e["launches"] += launches
         c.profile(False)
@@ -233,7 +274,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32 quantiser, i32/bit codec", "data": "synthetic",
         "config": {"workload": wl.name, "tensors": len(xs), "numel": total, "eb": eb, "radius": 512,
-                   "chunk": 4096, "sub": args.sub, "streams": S, "p_zero": wl.p_zero, "box_k": wl.k,
+                   "chunk": 4096, "sub": args.sub, "streams": S, "pipeline": pipeline, "p_zero": wl.p_zero, "box_k": wl.k,
                    "seed_base": wl.seed(0)},
         "compression_ratio": round(4.0 * total / comp_bytes, 4),
         "compressed_bytes_held": comp_bytes,

@@ -107,6 +107,21 @@ size_t cmp_bound(const cmp_ctx *ctx, const int64_t shape[4]);
 int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb,
                  void *d_out, size_t out_cap, size_t *h_size, void *stream);
 
+/* cmp_compress in two calls, for callers that pipeline tensors over several streams: the single
+ * workgroup that builds the Huffman codebook leaves the GPU idle, and with begin(i+1) issued on
+ * one stream while finish(i) runs on another the first sweep of the next tensor fills that time.
+ *   cmp_compress_begin   the first sweep (pre-quantisation, Lorenzo prediction, code / outlier
+ *                        split, histogram; Section 3.1) on `stream`;
+ *   cmp_compress_finish  codebook, bit-packing and outlier records into d_out, on `stream`, which
+ *                        may differ from the first one if the caller orders it after that call's
+ *                        work (an event).  d_x of the begin call is read again (outlier records)
+ *                        and must stay valid and unchanged until this work is done.
+ * A context holds one tensor at a time between the two calls: begin returns CMP_E_ARG while a
+ * previous begin has not been finished, finish without begin returns CMP_E_ARG.  The pair gives
+ * the same container as cmp_compress; h_size as there. */
+int cmp_compress_begin(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *stream);
+int cmp_compress_finish(cmp_ctx *ctx, void *d_out, size_t out_cap, size_t *h_size, void *stream);
+
 /* Waits for `stream`, reads the header of a container produced by cmp_compress
  * and stores its size in bytes (the compression-ratio monitor of Section 4.4
  * reads this).  Returns CMP_E_NOSPACE (h_size = bytes needed) if that compress

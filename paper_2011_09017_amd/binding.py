@@ -21,7 +21,8 @@ CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES, CMP_STAG
 
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
            "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",
-           "cmp_profile", "cmp_profile_read", "cmp_default_controller_config", "cmp_estimate_eb"]
+           "cmp_profile", "cmp_profile_read", "cmp_default_controller_config", "cmp_estimate_eb",
+           "cmp_compress_begin", "cmp_compress_finish"]
 
 
 class cmp_controller_config(C.Structure):
@@ -56,6 +57,8 @@ def lib() -> C.CDLL:
         L.cmp_last_status.argtypes = [vp, vp]; L.cmp_last_status.restype = i32
         L.cmp_debug_stage.argtypes = [vp, i32, vp, vp]; L.cmp_debug_stage.restype = i32
         L.cmp_strerror.argtypes = [i32]; L.cmp_strerror.restype = C.c_char_p
+        L.cmp_compress_begin.argtypes = [vp, vp, vp, C.c_float, vp]; L.cmp_compress_begin.restype = i32
+        L.cmp_compress_finish.argtypes = [vp, vp, sz, vp, vp]; L.cmp_compress_finish.restype = i32
         L.cmp_default_controller_config.argtypes = [vp]; L.cmp_default_controller_config.restype = None
         L.cmp_estimate_eb.argtypes = [vp, vp, C.c_uint64, vp, C.c_uint64, C.c_uint64, vp, C.c_uint64, vp, vp, vp, vp]
         L.cmp_estimate_eb.restype = i32
@@ -104,6 +107,18 @@ def cmp_compressed_size(ctx, d_buf: int, stream: int):
     size = C.c_size_t(0)
     rc = lib().cmp_compressed_size(ctx, d_buf, C.addressof(size), stream)
     return rc, int(size.value)
+
+
+def cmp_compress_begin(ctx, d_x: int, shape, eb: float, stream: int) -> int:
+    s = _shape4(shape)
+    return lib().cmp_compress_begin(ctx, d_x, C.addressof(s), C.c_float(eb), stream)
+
+
+def cmp_compress_finish(ctx, d_out: int, out_cap: int, want_size: bool, stream: int):
+    """Returns (rc, size or None)."""
+    n = C.c_size_t(0)
+    rc = lib().cmp_compress_finish(ctx, d_out, out_cap, C.addressof(n) if want_size else None, stream)
+    return rc, (int(n.value) if want_size else None)
 
 
 def cmp_decompress(ctx, d_buf: int, size: int, shape, eb: float, d_xout: int, stream: int) -> int:

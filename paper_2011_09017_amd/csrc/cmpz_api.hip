@@ -31,6 +31,8 @@ struct cmp_ctx {
     ControllerScratch *d_ctl;
     ControllerResult  *d_ctl_result;
     uint64_t   last_numel;
+    CompressArgs pending;       // what cmp_compress_begin left for cmp_compress_finish
+    bool       has_pending;
     Profiler   prof;
 };
 
@@ -139,6 +141,7 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     ctx->device = device;
     ctx->max_chunks = (c.max_numel + c.chunk - 1) / c.chunk;
     ctx->last_numel = 0;
+    ctx->has_pending = false;
 
     uint64_t off = 0;
     auto carve = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -198,26 +201,22 @@ size_t cmp_bound(const cmp_ctx *ctx, const int64_t shape[4])
     return (size_t)(l.off_payload + align_up(payload, 16) + 2 * align_up(4 * numel, 16));
 }
 
-int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *d_out,
-                 size_t out_cap, size_t *h_size, void *stream)
+namespace {
+
+// Argument checks and everything of CompressArgs that does not depend on the output buffer.
+int fill_compress_args(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, CompressArgs *out)
 {
     uint64_t numel;
     float s, r;
-    if (!ctx || !d_out || !shape_numel(shape, &numel)) return CMP_E_ARG;
+    if (!ctx || !shape_numel(shape, &numel)) return CMP_E_ARG;
     if (numel > ctx->cfg.max_numel || (numel > 0 && !d_x)) return CMP_E_ARG;
     if (!constants(eb, ctx->cfg.guard_shift, &s, &r)) return CMP_E_ARG;
-    if ((reinterpret_cast<uintptr_t>(d_x) & 15) || (reinterpret_cast<uintptr_t>(d_out) & 15)) return CMP_E_ARG;
+    if (reinterpret_cast<uintptr_t>(d_x) & 15) return CMP_E_ARG;
 
     CompressArgs a;
     std::memset(&a, 0, sizeof(a));
     a.lay = make_layout(numel, ctx->cfg);
-    if (out_cap < a.lay.off_payload) {
-        if (h_size) *h_size = (size_t)a.lay.off_payload;
-        return CMP_E_NOSPACE;
-    }
     a.x = d_x;
-    a.out = static_cast<uint8_t *>(d_out);
-    a.out_cap = out_cap;
     a.numel = (uint32_t)numel;
     a.H = (uint32_t)shape[2]; a.W = (uint32_t)shape[3]; a.HW = a.H * a.W;
     for (int i = 0; i < 4; ++i) a.shape[i] = (uint32_t)shape[i];
@@ -232,12 +231,73 @@ int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float e
     a.tile_chunks = 8;
     while (a.tile_chunks > 1 && (a.lay.nchunks + a.tile_chunks - 1) / a.tile_chunks < 768) a.tile_chunks >>= 1;
     a.meta = ctx->d_meta; a.status = ctx->d_status;
+    *out = a;
+    return CMP_OK;
+}
+
+}  // namespace
+
+int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *d_out,
+                 size_t out_cap, size_t *h_size, void *stream)
+{
+    CompressArgs a;
+    if (!d_out || (reinterpret_cast<uintptr_t>(d_out) & 15)) return CMP_E_ARG;
+    const int rc = fill_compress_args(ctx, d_x, shape, eb, &a);
+    if (rc != CMP_OK) return rc;
+    if (ctx->has_pending) return CMP_E_ARG;                  // between cmp_compress_begin and _finish
+    if (out_cap < a.lay.off_payload) {
+        if (h_size) *h_size = (size_t)a.lay.off_payload;
+        return CMP_E_NOSPACE;
+    }
+    a.out = static_cast<uint8_t *>(d_out);
+    a.out_cap = out_cap;
 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    launch_compress(a, &ctx->prof, st);
-    ctx->last_numel = numel;
+    launch_compress_begin(a, &ctx->prof, st);
+    launch_compress_finish(a, &ctx->prof, st);
+    ctx->last_numel = a.numel;
+    if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
+    if (h_size) return cmp_compressed_size(ctx, d_out, h_size, stream);
+    return CMP_OK;
+}
+
+int cmp_compress_begin(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *stream)
+{
+    CompressArgs a;
+    const int rc = fill_compress_args(ctx, d_x, shape, eb, &a);
+    if (rc != CMP_OK) return rc;
+    if (ctx->has_pending) return CMP_E_ARG;                  // the previous begin was never finished
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    launch_compress_begin(a, &ctx->prof, static_cast<hipStream_t>(stream));
+    if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
+    ctx->pending = a;
+    ctx->has_pending = true;
+    return CMP_OK;
+}
+
+int cmp_compress_finish(cmp_ctx *ctx, void *d_out, size_t out_cap, size_t *h_size, void *stream)
+{
+    if (!ctx || !ctx->has_pending) return CMP_E_ARG;
+    if (!d_out || (reinterpret_cast<uintptr_t>(d_out) & 15)) return CMP_E_ARG;
+    CompressArgs a = ctx->pending;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ctx->has_pending = false;
+    if (out_cap < a.lay.off_payload) {
+        // nothing can be written; drop what the first sweep accumulated so that the context is clean
+        if (hipMemsetAsync(ctx->d_hist, 0, 4 * kMaxSym * kHistCopies, st) != hipSuccess) return CMP_E_HIP;
+        if (hipMemsetAsync(ctx->d_meta + kMetaRangeEvents, 0, 4, st) != hipSuccess) return CMP_E_HIP;
+        if (h_size) *h_size = (size_t)a.lay.off_payload;
+        return CMP_E_NOSPACE;
+    }
+    a.out = static_cast<uint8_t *>(d_out);
+    a.out_cap = out_cap;
+    launch_compress_finish(a, &ctx->prof, st);
+    ctx->last_numel = a.numel;
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
     if (h_size) return cmp_compressed_size(ctx, d_out, h_size, stream);
     return CMP_OK;

@@ -654,16 +654,23 @@ __global__ void k_empty_container(CompressArgs a)
 
 }  // namespace
 
-void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st)
+// Sweep 1 alone (nothing for an empty tensor).
+void launch_compress_begin(const CompressArgs &a, Profiler *prof, hipStream_t st)
+{
+    if (a.numel == 0) return;
+    const uint32_t tiles = (a.lay.nchunks + kTileChunks - 1) / kTileChunks;
+    if (!launch_sweep1_tiled(a, prof, st))
+        launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist, dim3(tiles), dim3(kThreads), st, a);
+}
+
+// Codebook, sweep 2 and the outlier records, from what sweep 1 left in the scratch.
+void launch_compress_finish(const CompressArgs &a, Profiler *prof, hipStream_t st)
 {
     if (a.numel == 0) {
         launch(prof, kKEmpty, k_empty_container, dim3(1), dim3(256), st, a);
         return;
     }
     const uint32_t nchunks = a.lay.nchunks;
-    const uint32_t tiles = (nchunks + kTileChunks - 1) / kTileChunks;
-    if (!launch_sweep1_tiled(a, prof, st))
-        launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist, dim3(tiles), dim3(kThreads), st, a);
     launch_codebook(a, prof, st);
     const uint32_t ntiles = (nchunks + a.tile_chunks - 1) / a.tile_chunks;
     // every workgroup costs a ticket, a look-back over the tiles in flight and a code table load:

@@ -229,7 +229,8 @@ inline void launch(Profiler *p, int id, K kernel, dim3 grid, dim3 block, hipStre
     }
 }
 
-void launch_compress(const CompressArgs &a, Profiler *prof, hipStream_t st);
+void launch_compress_begin(const CompressArgs &a, Profiler *prof, hipStream_t st);
+void launch_compress_finish(const CompressArgs &a, Profiler *prof, hipStream_t st);
 void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st);
 bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st);
 size_t decode_tables_bytes();

@@ -263,6 +263,36 @@ def test_determinism_and_context_reuse(gpu, orc):
 FULL = [("cfg2_vgg16_conv1_2", 0), ("cfg3_resnet50_bottleneck", 0), ("cfg4_alexnet_conv1", 0)]
 
 
+def test_compress_in_two_calls_on_two_streams(gpu, orc):
+    """cmp_compress_begin on one stream, cmp_compress_finish on another (ordered by an event): the same
+    container as the single call; misuse of the pair is refused."""
+    ctx = make_ctx(gpu)
+    x = activation((3, 8, 40, 24), 5, 0.5, 424242, device="cuda")
+    eb = 1e-2
+    ref, ref_size, rc = ctx.compress(x, eb)
+    assert rc == 0
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    s1.wait_stream(torch.cuda.current_stream())
+    out = torch.zeros_like(ref)
+    assert gpu.cmp_compress_finish(ctx._h, out.data_ptr(), out.numel(), False, s2.cuda_stream)[0] == gpu.CMP_E_ARG
+    assert gpu.cmp_compress_begin(ctx._h, x.data_ptr(), x.shape, eb, s1.cuda_stream) == 0
+    assert gpu.cmp_compress_begin(ctx._h, x.data_ptr(), x.shape, eb, s1.cuda_stream) == gpu.CMP_E_ARG
+    assert gpu.cmp_compress(ctx._h, x.data_ptr(), x.shape, eb, out.data_ptr(), out.numel(), False,
+                            s1.cuda_stream)[0] == gpu.CMP_E_ARG
+    ev = torch.cuda.Event()
+    ev.record(s1)
+    s2.wait_event(ev)
+    rc, size = gpu.cmp_compress_finish(ctx._h, out.data_ptr(), out.numel(), True, s2.cuda_stream)
+    assert rc == 0 and size == ref_size
+    assert torch.equal(out[:size], ref[:size])
+    # too small an output: refused, and the context is clean for the next tensor
+    assert gpu.cmp_compress_begin(ctx._h, x.data_ptr(), x.shape, eb, s1.cuda_stream) == 0
+    s1.synchronize()
+    assert gpu.cmp_compress_finish(ctx._h, out.data_ptr(), 64, False, s1.cuda_stream)[0] == gpu.CMP_E_NOSPACE
+    s1.synchronize()
+    check_case(gpu, orc, x.cpu().numpy(), eb, ctx, orc.Config())
+
+
 @pytest.mark.parametrize("name,ti", FULL)
 def test_full_size_configs_bit_exact(gpu, orc, name, ti):
     """BASELINE configs 2-4 at full size: whole container and whole reconstruction, byte for byte."""
