@@ -24,6 +24,11 @@ constexpr uint32_t kInf = 0xffffffffu;       // "queue empty"; a real weight rea
 #define PHASE(k)
 #endif
 
+__device__ __forceinline__ uint32_t rdlane(uint32_t v, uint32_t l)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)l);
+}
+
 __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
 {
 #ifdef CMPZ_PHASE_CLOCKS
@@ -85,40 +90,113 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
     __syncthreads();
 
     PHASE(2)
-    // 4. two-queue merge by wave 0 with uniform (scalar) control flow and no LDS traffic in
-    //    the common step.  Lane j of LB holds the weight of leaf lbase+j, lane j of IB that of
-    //    internal node ibase+j (kInf = not made yet); the queue heads are read with v_readlane.
-    //    Step m makes internal node m; its weight and its two children are logged in lane m%64
-    //    of WLOG / PLOG, which are written to LDS once per 64 steps.
-    if (wv == 0 && n >= 2) {
+    // 4. two-queue merge by wave 0.  Lane j of LB holds the weight of leaf lbase+j, lane j of IB
+    //    that of internal node ibase+j (kInf = not made yet).  The two lightest unused nodes of
+    //    either queue are kept in scalar registers; step m makes internal node m and logs its
+    //    weight and its two children in lane m%64 of WLOG / PLOG, which go to LDS once per 64
+    //    steps.  A lone wave pays about six cycles per instruction whatever its kind, so the steps
+    //    between two window slides run in a hand-written loop of about 25 scalar and lane
+    //    instructions (the compiler's version of the same step has about 70).
+    if (__builtin_amdgcn_readfirstlane(wv) == 0 && __builtin_amdgcn_readfirstlane((int)n) >= 2) {
         uint32_t LB = leaf_w[lane], IB = kInf, WLOG = kInf, PLOG = 0;
-        uint32_t lbase = 0, ibase = 0, ql = 0, qi = 0;
-        const uint32_t steps = n - 1;
-        for (uint32_t m = 0; m < steps; ++m) {
-            // rare: slide a window, or start a new log block
-            if (ql + 1 - lbase >= 64) { lbase = ql; LB = leaf_w[ql + lane]; }
+        uint32_t lbase = 0, ibase = 0, ql = 0, qi = 0, m = 0;
+        uint32_t l0 = rdlane(LB, 0), l1 = rdlane(LB, 1), i0 = kInf, i1 = kInf;
+        const uint32_t nu = (uint32_t)__builtin_amdgcn_readfirstlane((int)n);   // n came from LDS: tell the compiler it is uniform
+        const uint32_t steps = nu - 1;
+        while (m < steps) {
+            // rare: start a new log block, slide a window (heads are re-read from the new window)
             if ((m & 63u) == 0 && m != 0) {
                 node_w[m - 64 + lane] = WLOG; merge_log[m - 64 + lane] = PLOG;
                 WLOG = kInf;
             }
-            if (qi + 1 - ibase >= 64) {
+            if (ql - lbase >= 32) {
+                lbase = ql; LB = leaf_w[ql + lane];
+                l0 = rdlane(LB, 0); l1 = rdlane(LB, 1);
+            }
+            if (qi - ibase >= 32) {
                 // every node made so far must be readable from LDS: flush the open log block too
                 node_w[(m & ~63u) + lane] = WLOG;
                 ibase = qi;
                 IB = node_w[qi + lane];                     // entries at or past m are still kInf
+                i0 = rdlane(IB, 0); i1 = rdlane(IB, 1);
             }
-            const uint32_t l0 = (uint32_t)__builtin_amdgcn_readlane((int)LB, (int)(ql - lbase));
-            const uint32_t l1 = (uint32_t)__builtin_amdgcn_readlane((int)LB, (int)(ql + 1 - lbase));
-            const uint32_t i0 = (uint32_t)__builtin_amdgcn_readlane((int)IB, (int)(qi - ibase));
-            const uint32_t i1 = (uint32_t)__builtin_amdgcn_readlane((int)IB, (int)(qi + 1 - ibase));
-            uint32_t wsum, kids;                             // children ids, low and high half
-            if (l1 <= i0) { wsum = l0 + l1; kids = ql | ((ql + 1) << 16); ql += 2; }              // two leaves (a leaf wins ties)
-            else if (i1 < l0) { wsum = i0 + i1; kids = (n + qi) | ((n + qi + 1) << 16); qi += 2; } // two internal nodes
-            else { wsum = l0 + i0; kids = ql | ((n + qi) << 16); ql += 1; qi += 1; }              // one of each
-            const uint32_t slot = m & 63u;
-            WLOG = ((uint32_t)lane == slot) ? wsum : WLOG;
-            PLOG = ((uint32_t)lane == slot) ? kids : PLOG;
-            IB = ((uint32_t)lane == m - ibase) ? wsum : IB;  // m - ibase >= 64 selects no lane
+            uint32_t lrel = ql - lbase, irel = qi - ibase, slot = m & 63u, mrel = m - ibase;
+            // steps that need no slide and no flush: both windows are read at most one lane past
+            // their head, which advances by at most two per step
+            uint32_t cnt = steps - m;
+            cnt = cnt < 64 - slot ? cnt : 64 - slot;
+            cnt = cnt < (62 - lrel) / 2 ? cnt : (62 - lrel) / 2;
+            cnt = cnt < (62 - irel) / 2 ? cnt : (62 - irel) / 2;
+            m += cnt;
+            // every scalar operand of the loop below, made provably uniform (a few moves per ~20 steps)
+            auto uni = [](uint32_t &v) { v = (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
+            uni(l0); uni(l1); uni(i0); uni(i1); uni(ql); uni(qi); uni(lrel); uni(irel); uni(slot); uni(mrel); uni(cnt);
+            uint32_t t1, t2, ws, kd, m0_saved;
+            asm volatile(
+                "s_mov_b32 %[sv], m0\n"
+                "s_nop 3\n"                                        // lane selects below were written by vector moves
+                "1:\n"
+                "  s_cmp_le_u32 %[l1], %[i0]\n"                    // a leaf wins ties
+                "  s_cbranch_scc0 2f\n"
+                "  s_add_u32 %[ws], %[l0], %[l1]\n"               // two leaves
+                "  s_add_u32 %[t1], %[ql], 1\n"
+                "  s_lshl_b32 %[t1], %[t1], 16\n"
+                "  s_or_b32 %[kd], %[t1], %[ql]\n"
+                "  s_add_u32 %[ql], %[ql], 2\n"
+                "  s_add_u32 %[lrel], %[lrel], 2\n"
+                "  s_add_u32 %[t1], %[lrel], 1\n"
+                "  v_readlane_b32 %[l0], %[LB], %[lrel]\n"
+                "  v_readlane_b32 %[l1], %[LB], %[t1]\n"
+                "  s_branch 4f\n"
+                "2:\n"
+                "  s_cmp_lt_u32 %[i1], %[l0]\n"
+                "  s_cbranch_scc0 3f\n"
+                "  s_add_u32 %[ws], %[i0], %[i1]\n"               // two internal nodes
+                "  s_add_u32 %[t1], %[n], %[qi]\n"
+                "  s_add_u32 %[t2], %[t1], 1\n"
+                "  s_lshl_b32 %[t2], %[t2], 16\n"
+                "  s_or_b32 %[kd], %[t2], %[t1]\n"
+                "  s_add_u32 %[qi], %[qi], 2\n"
+                "  s_add_u32 %[irel], %[irel], 2\n"
+                "  s_branch 4f\n"
+                "3:\n"
+                "  s_add_u32 %[ws], %[l0], %[i0]\n"               // one of each
+                "  s_add_u32 %[t1], %[n], %[qi]\n"
+                "  s_lshl_b32 %[t1], %[t1], 16\n"
+                "  s_or_b32 %[kd], %[t1], %[ql]\n"
+                "  s_add_u32 %[ql], %[ql], 1\n"
+                "  s_add_u32 %[qi], %[qi], 1\n"
+                "  s_add_u32 %[lrel], %[lrel], 1\n"
+                "  s_add_u32 %[irel], %[irel], 1\n"
+                "  s_mov_b32 %[l0], %[l1]\n"
+                "  s_add_u32 %[t1], %[lrel], 1\n"
+                "  v_readlane_b32 %[l1], %[LB], %[t1]\n"
+                "4:\n"
+                "  s_mov_b32 m0, %[slot]\n"                        // log node m
+                "  s_nop 0\n"
+                "  v_writelane_b32 %[WL], %[ws], m0\n"
+                "  v_writelane_b32 %[PL], %[kd], m0\n"
+                "  s_cmp_lt_u32 %[mrel], 64\n"
+                "  s_cbranch_scc0 5f\n"
+                "  s_mov_b32 m0, %[mrel]\n"                        // and make it visible to the internal queue
+                "  s_nop 0\n"
+                "  v_writelane_b32 %[IB], %[ws], m0\n"
+                "5:\n"
+                "  s_add_u32 %[t1], %[irel], 1\n"
+                "  v_readlane_b32 %[i0], %[IB], %[irel]\n"
+                "  v_readlane_b32 %[i1], %[IB], %[t1]\n"
+                "  s_add_u32 %[slot], %[slot], 1\n"
+                "  s_add_u32 %[mrel], %[mrel], 1\n"
+                "  s_sub_u32 %[cnt], %[cnt], 1\n"
+                "  s_cmp_lg_u32 %[cnt], 0\n"
+                "  s_cbranch_scc1 1b\n"
+                "  s_mov_b32 m0, %[sv]\n"
+                : [l0] "+s"(l0), [l1] "+s"(l1), [i0] "+s"(i0), [i1] "+s"(i1), [ql] "+s"(ql), [qi] "+s"(qi),
+                  [lrel] "+s"(lrel), [irel] "+s"(irel), [slot] "+s"(slot), [mrel] "+s"(mrel), [cnt] "+s"(cnt),
+                  [IB] "+v"(IB), [WL] "+v"(WLOG), [PL] "+v"(PLOG),
+                  [t1] "=&s"(t1), [t2] "=&s"(t2), [ws] "=&s"(ws), [kd] "=&s"(kd), [sv] "=&s"(m0_saved)
+                : [LB] "v"(LB), [n] "s"(nu)
+                : "scc", "memory");
         }
         const uint32_t blk = (steps - 1) & ~63u;             // the open log block
         node_w[blk + lane] = WLOG; merge_log[blk + lane] = PLOG;
