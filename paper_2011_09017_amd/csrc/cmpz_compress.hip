@@ -201,19 +201,18 @@ __device__ __forceinline__ uint64_t wave_desc_sum(uint64_t d, bool take)
 
 constexpr uint32_t kSpinLimit = 1u << 22;          // polls before a look-back gives up
 
-// Exclusive prefix (units, outliers) of chunk c from the descriptors of its predecessors;
+// Exclusive prefix (units, outliers) of tile c from the descriptors of its predecessors;
 // one wave, every lane inspects one predecessor per round (single-pass scan with look-back).
-// Chunks are handed out in index order, so every predecessor is owned by a workgroup that
+// Tiles are handed out in index order, so every predecessor is owned by a workgroup that
 // is already running and publishes without waiting on anyone: the wait always ends.  The
 // poll limit only guards against a defect; on expiry *failed is set and 0 returned.
-__device__ __forceinline__ uint64_t look_back(const uint64_t *desc, uint32_t c, int lane, bool *failed)
+// Starts at predecessor j with `excl` already summed over the tiles above j.
+__device__ __forceinline__ uint64_t look_back_from(const uint64_t *desc, int64_t j, uint64_t excl, int lane, bool *failed)
 {
-    uint64_t excl = 0;
-    int64_t j = (int64_t)c - 1;                    // nearest predecessor not yet accounted for
     uint32_t spins = 0;
     while (j >= 0) {
         const int64_t idx = j - lane;
-        const uint64_t d = (idx >= 0) ? desc_load(desc + idx) : kDescPrefix;   // before chunk 0: prefix 0
+        const uint64_t d = (idx >= 0) ? desc_load(desc + idx) : kDescPrefix;   // before tile 0: prefix 0
         const uint32_t state = (uint32_t)(d >> 62);
         const unsigned long long inv = __ballot(state == 0);
         const unsigned long long pre = __ballot(state == 2);
@@ -232,6 +231,46 @@ __device__ __forceinline__ uint64_t look_back(const uint64_t *desc, uint32_t c, 
         __builtin_amdgcn_s_sleep(2);
     }
     return excl;
+}
+
+// The descriptors of the kSnapRounds * 64 nearest predecessors of tile c, fetched in one go.  The
+// loads are issued where the snapshot is taken and their latency passes while the workgroup
+// packs; what the snapshot cannot settle (a predecessor that had not published yet, or no
+// prefix that near) is looked up again when the offset is needed.
+constexpr int kSnapRounds = 2;
+struct DescSnapshot {
+    uint64_t d[kSnapRounds];
+};
+__device__ __forceinline__ DescSnapshot look_back_snapshot(const uint64_t *desc, uint32_t c, int lane)
+{
+    DescSnapshot sn;
+#pragma unroll
+    for (int r = 0; r < kSnapRounds; ++r) {
+        const int64_t idx = (int64_t)c - 1 - r * kWave - lane;
+        sn.d[r] = (idx >= 0) ? desc_load(desc + idx) : kDescPrefix;
+    }
+    return sn;
+}
+__device__ __forceinline__ uint64_t look_back_finish(const uint64_t *desc, uint32_t c, const DescSnapshot &sn, int lane,
+                                                     bool *failed)
+{
+    uint64_t excl = 0;
+    int64_t j = (int64_t)c - 1;
+#pragma unroll
+    for (int r = 0; r < kSnapRounds; ++r) {
+        if (j < 0) return excl;
+        const uint64_t d = sn.d[r];
+        const uint32_t state = (uint32_t)(d >> 62);
+        const unsigned long long inv = __ballot(state == 0);
+        const unsigned long long pre = __ballot(state == 2);
+        const int first_inv = inv ? __ffsll((long long)inv) - 1 : 64;
+        const int first_pre = pre ? __ffsll((long long)pre) - 1 : 64;
+        if (first_pre < first_inv) return excl + wave_desc_sum(d, lane <= first_pre);
+        excl += wave_desc_sum(d, lane < first_inv);
+        j -= first_inv;
+        if (first_inv < 64) break;                 // not published when the snapshot was taken
+    }
+    return look_back_from(desc, j, excl, lane, failed);
 }
 
 // ---------------------------------------------------------------------------
@@ -424,20 +463,36 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
             }
         }
         PHASE(2)
-        // ---- publish the tile's size; wave 0 then finds the tile's offset by look-back ----
+        // ---- publish the tile's size and fetch the predecessors' descriptors; the tile's offset is
+        //      settled from them later, by wave 0, while the workgroup is packing ----
+        DescSnapshot snap;
+        uint32_t oc = 0, oinc = 0, tile_outl = 0;
+        bool settled = false;                        // wave 0: s_excl and the offset tables are written
         if (wv == 0) {
-            const uint32_t oc = (lane < (int)nq) ? a.outl_cnt[c0 + lane] : 0u;
-            const uint32_t oinc = wave_inclusive_sum(oc);
-            const uint32_t tile_outl = (uint32_t)__builtin_amdgcn_readlane((int)oinc, 63);
+            oc = (lane < (int)nq) ? a.outl_cnt[c0 + lane] : 0u;
+            oinc = wave_inclusive_sum(oc);
+            tile_outl = (uint32_t)__builtin_amdgcn_readlane((int)oinc, 63);
             const uint64_t own = ((uint64_t)tile_units << 32) | tile_outl;
             if (lane == 0) desc_store(a.desc + t, kDescAgg | own);
-            const uint64_t excl = look_back(a.desc, t, lane, &failed);
+            snap = look_back_snapshot(a.desc, t, lane);
+        }
+        auto settle = [&]() {                        // wave 0 only
+            if (settled) return;
+            settled = true;
+            const uint64_t own = ((uint64_t)tile_units << 32) | tile_outl;
+            const uint64_t excl = look_back_finish(a.desc, t, snap, lane, &failed);
             if (lane == 0) {
                 s_excl = excl;
                 // publish the inclusive prefix even after a failure so that successors do not wait
                 desc_store(a.desc + t, kDescPrefix | ((excl + own) & kDescMask));
             }
-            if (lane < (int)nq) outl_off[c0 + lane] = (uint32_t)excl + oinc - oc;
+            // where the tile's chunks and their outlier records start
+            const uint32_t uq = (lane < (int)nq) ? s_units[lane] : 0u;
+            const uint32_t uinc = wave_inclusive_sum(uq);
+            if (lane < (int)nq) {
+                outl_off[c0 + lane] = (uint32_t)excl + oinc - oc;
+                chunk_off[c0 + lane] = (uint32_t)(excl >> 32) + uinc - uq;
+            }
             if (c0 + nq == nchunks && lane == 0) {
                 // end markers, zero padding of both tables, and the totals for the header
                 const uint32_t padded = (nchunks + 1 + 3) & ~3u;
@@ -448,7 +503,7 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
                 a.meta[kMetaTotalUnits] = tot_u;
                 a.meta[kMetaNOutliers] = tot_o;
             }
-        }
+        };
 
         PHASE(3)
         // ---- pack and store: consecutive chunks share the LDS image while they fit ----
@@ -478,13 +533,13 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
             const uint32_t uq = s_units[q];
             if (uq > kImageUnits) { failed = true; return; }          // cannot happen for counts below 2^32
             if (u_img + uq > kImageUnits) {          // image full: store it and start afresh
+                if (wv == 0) settle();
                 __syncthreads();
                 store_image();
                 __syncthreads();
                 zero_image();
                 __syncthreads();
             }
-            if (tid == 0) chunk_off[c0 + q] = (uint32_t)(s_excl >> 32) + u_done + u_img;
             const uint32_t p0 = u_img * 128u + pos_q;                 // bit position in the image
             if (short_codes) {
                 uint32_t pos = p0;
@@ -517,8 +572,10 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
         };
         if (short_codes) {
 #pragma unroll
-            for (int q = 0; q < kTileMax; ++q)
+            for (int q = 0; q < kTileMax; ++q) {
                 if (q < (int)nq) pack_chunk(q, sv[q][0], sv[q][1], r.pos[q]);     // uniform
+                if (q == 1 && wv == 0) settle();     // the descriptors have arrived by now; successors want the prefix
+            }
         } else {
 #pragma unroll 1
             for (int q = 0; q < kTileMax; ++q) {
@@ -530,8 +587,9 @@ __global__ __launch_bounds__(kThreads) void k_encode(CompressArgs a)
                 r.rotate();
             }
         }
+        if (wv == 0) settle();
         PHASE(4)
-        __syncthreads();                             // image complete
+        __syncthreads();                             // image complete, s_excl visible
         store_image();
         PHASE(5)
     }
