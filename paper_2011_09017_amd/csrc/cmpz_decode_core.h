@@ -333,10 +333,8 @@ __device__ __forceinline__ uint32_t decode_run(const DecodeTables &T, RD rd, uin
 // bit `pos` on and calls put(k, residual) for k >= skip; returns the bit position after the last
 // codeword.
 //
-// LDS reads at any bit position are cheap, so there is no bit window to carry along and refill:
-// every codeword is looked up from the two words around its own position.  The 32 bits from
-// position p on are alignbit(S[j], S[j+1], -p mod 32) with j = (p + 31) / 32 - 1 (stream words):
-// counted this way the shift stays below 32 also when p is a multiple of 32.
+// The 32 bits from position p on are alignbit(S[j], S[j+1], -p mod 32) with j = (p + 31) / 32 - 1
+// (stream words): counted this way the shift stays below 32 also when p is a multiple of 32.
 // A corrupted stream cannot run out of the staged range: word indices are clamped.
 constexpr int kStagePad = 4;
 template <class PUT>
@@ -346,12 +344,18 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
     const uint32_t t32 = T.t32, sh = T.sh, has_long = T.has_long;
     const uint32_t jmax = wmax + 1;
     const char *t1 = reinterpret_cast<const char *>(T.t1);
+    // The three stream words around the position live in registers: wa, wb are the window of the
+    // current codeword, wc the word after them.  A codeword of the first two table levels is at
+    // most 27 bits long, so the window moves on by one word at most, and the word that then
+    // becomes wc is fetched a whole step before it can be needed: the only LDS access a step
+    // has to wait for is the table look-up.
+    uint32_t npos = 0u - pos;                                 // alignbit takes its shift from -pos mod 32
+    uint32_t J = (31u - npos) >> 5;                           // stream word J-1 holds bit pos (or ends just before it)
+    J = J < jmax ? J : jmax;
+    uint32_t wa = S[kStagePad - 1 + J], wb = S[kStagePad + J], wc = S[kStagePad + 1 + J];
 #pragma unroll 4
     for (uint32_t k = 0; k < count; ++k) {
-        uint32_t j = (pos + 31u) >> 5;                        // stream word j-1 holds bit pos (or ends just before it)
-        j = j < jmax ? j : jmax;
-        const uint32_t w0 = S[kStagePad - 1 + j], w1 = S[kStagePad + j];
-        const uint32_t hi = __builtin_amdgcn_alignbit(w0, w1, 0u - pos);
+        const uint32_t hi = __builtin_amdgcn_alignbit(wa, wb, npos);
         uint32_t e = *reinterpret_cast<const uint16_t *>(t1 + ((hi >> (31 - kLB)) & (2u * kT1Size - 2u)));
         if (e == 0) {
             if (has_long) {
@@ -361,7 +365,7 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
             }
             if (e == 0) {
                 // canonical search over the longer lengths on a 64-bit window
-                const uint32_t lo = __builtin_amdgcn_alignbit(w1, S[kStagePad + 1 + j], 0u - pos);
+                const uint32_t lo = __builtin_amdgcn_alignbit(wb, wc, npos);
                 const uint64_t v = (((uint64_t)hi) << 32) | lo;
                 uint32_t len = 0, sy = 0;                     // no match: residual 0
                 for (uint32_t L = kLB + 1; L <= T.max_len; ++L) {
@@ -374,12 +378,23 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
                 }
                 if (len == 0) { bad = true; len = 1; }
                 e = sy | (len << 10);
+                // such a codeword may end two words further on: take the first of the two moves here
+                uint32_t Jf = (31u - (npos - len)) >> 5;
+                Jf = Jf < jmax ? Jf : jmax;
+                if (Jf > J + 1) { wa = wb; wb = wc; wc = S[kStagePad + 2 + J]; ++J; }
             }
         }
-        pos += e >> 10;
+        npos -= e >> 10;
+        uint32_t Jn = (31u - npos) >> 5;
+        Jn = Jn < jmax ? Jn : jmax;
+        const bool moved = Jn != J;
+        wa = moved ? wb : wa;
+        wb = moved ? wc : wb;
+        wc = S[kStagePad + 1 + Jn];
+        J = Jn;
         if (k >= skip) put(k, entry_residual(e));
     }
-    return pos;
+    return 0u - npos;
 }
 
 }  // namespace cmpz
