@@ -66,7 +66,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg5_resnet18_stream")
     ap.add_argument("--eb", type=float, default=None)
     ap.add_argument("--sub", type=int, default=32, help="codes per sub-block (decode parallelism vs. 16 bits of metadata each)")
-    ap.add_argument("--streams", type=int, default=3, help="contexts/streams the tensors are dealt over, round robin")
+    ap.add_argument("--streams", type=int, default=6, help="contexts/streams the tensors are dealt over, round robin")
     ap.add_argument("--contexts", type=int, default=6, help="compress contexts (tensors in flight) of the pipelined schedule")
     ap.add_argument("--pipeline", action="store_true",
                     help="all first sweeps (cmp_compress_begin) on one stream and the codebook / second sweep "

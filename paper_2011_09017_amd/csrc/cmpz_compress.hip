@@ -732,9 +732,11 @@ void launch_compress_finish(const CompressArgs &a, Profiler *prof, hipStream_t s
     launch_codebook(a, prof, st);
     const uint32_t ntiles = (nchunks + a.tile_chunks - 1) / a.tile_chunks;
     // every workgroup costs a ticket, a look-back over the tiles in flight and a code table load:
-    // about one workgroup per 16 chunks, between one and three (what fits) per CU
+    // about one workgroup per 16 chunks, between one and two per CU.  Three would fit and are a
+    // little faster when the kernel has the chip to itself; two leave registers for the first
+    // sweep of another stream's tensor beside it, which is worth more.
     uint32_t egrid = nchunks / 16;
-    egrid = egrid < 256u ? 256u : egrid > 768u ? 768u : egrid;
+    egrid = egrid < 256u ? 256u : egrid > 512u ? 512u : egrid;
     egrid = egrid < ntiles ? egrid : ntiles;
     launch(prof, kKEncode, k_encode, dim3(egrid), dim3(kThreads), st, a);
     launch(prof, kKOutliers, k_outliers, dim3(nchunks), dim3(kThreads), st, a);
