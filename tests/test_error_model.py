@@ -1,0 +1,159 @@
+"""Synthetic validation of the gradient-error model (Section 3.2; Eq. 1, 3, 4, 5, 9).
+
+A convolution's weight gradient is linear in the saved activation (Eq. 1), so the gradient error
+caused by compressing the activation is the same convolution applied to the activation error
+(Eq. 3): E = sum over batch and positions of e * L.  With e uniform on [-eb_in, eb_in] and
+independent of L (Section 3.1) every element of E has the variance
+
+    sigma^2 = eb_in^2 / 3 * sum(L^2 over the loss elements it combines with a non-zero activation)
+
+and, being a sum of many independent terms, is normal (Eq. 4).  That closed form is what the
+measured sigma is checked against; the paper's own estimator sigma ~ a * Lbar * sqrt(N) * eb (Eq. 5)
+is a heuristic whose constant depends on the layer, so it is only reported and checked to be of
+the right order ("parity unpinned" for a).  What the laws in the text fix is checked:
+* the share of E within +-sigma is 68.2 % (normal distribution),
+* sigma grows with sqrt(2) for a doubled batch (the gradient summed, not averaged, over the batch),
+* sigma is proportional to eb,
+* zeros stay zero through the compressor, and sigma' = sigma * sqrt(R) for a non-zero fraction R (Eq. 9).
+
+Inputs: activations N(0,1) (or ReLU-like with exact zeros), loss a cubed normal (concentrated at
+zero with a few large values, as Section 3.2 describes); seeded.  The CPU test runs the oracle on a
+small layer, the GPU test the HIP path on a 64x64x28x28 layer.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+
+def make_layer(seed, n, c, k, hw, p_zero=0.0):
+    g = torch.Generator().manual_seed(seed)
+    act = torch.randn(n, c, hw, hw, generator=g, dtype=torch.float32)
+    if p_zero > 0:
+        act = act * (torch.rand(n, c, hw, hw, generator=g) >= p_zero)
+    z = torch.randn(n, k, hw, hw, generator=g, dtype=torch.float64)
+    loss = (z ** 3 * 1e-3)
+    return act.contiguous(), loss.contiguous()
+
+
+def weight_grad(a64, loss64):
+    """Weight gradient of a 3x3, stride 1, pad 1 convolution, summed over the batch (Eq. 1):
+    every output position's loss times the 3x3 input patch under it, as one matrix product per
+    sample over the unfolded input (fp64 throughout)."""
+    k, c = loss64.shape[1], a64.shape[1]
+    cols = F.unfold(a64, kernel_size=3, padding=1)                 # (n, c*9, positions)
+    g = torch.einsum("nkp,ncp->kc", loss64.flatten(2), cols)
+    return g.reshape(k, c, 3, 3)
+
+
+def exact_sigma(act, loss64, eb_in):
+    """Per gradient element: eb_in^2/3 * sum of L^2 over the terms with a non-zero activation;
+    returned as the root of its mean over the gradient elements."""
+    mask = (act != 0).to(torch.float64)
+    var = weight_grad(mask, loss64 ** 2) * (eb_in ** 2 / 3.0)
+    return math.sqrt(float(var.mean()))
+
+
+def eb_inner(eb):
+    eb32 = np.float32(eb)
+    return float(eb32 - np.ldexp(eb32, -7))            # the guard band of the pre-quantisation
+
+
+def gradient_error(act, rec, loss64):
+    e = rec.to(torch.float64) - act.to(torch.float64)
+    return weight_grad(e, loss64)
+
+
+def check_model(act, rec, loss64, eb, rel):
+    assert float((rec.double() - act.double()).abs().max()) <= float(np.float32(eb))
+    assert bool((rec[act == 0] == 0).all()), "zeros must stay zero"
+    E = gradient_error(act, rec, loss64).flatten()
+    sig = float(E.std())
+    ref = exact_sigma(act, loss64, eb_inner(eb))
+    assert sig == pytest.approx(ref, rel=rel)
+    assert abs(float(E.mean())) < 5 * sig / math.sqrt(E.numel())
+    return sig, E
+
+
+# ---------------------------------------------------------------------------------------------
+def test_oracle_error_model_small_layer():
+    from oracle import compress, decompress
+    eb = 1e-2
+    act, loss = make_layer(11, 16, 8, 8, 16)
+
+    def through(a):
+        rc, buf, size, _ = compress(a.numpy(), eb)
+        assert rc >= 0
+        rc, out = decompress(buf, a.shape, eb)
+        assert rc == 0
+        return torch.from_numpy(out)
+
+    # 8*8*9 = 576 gradient elements: sigma of the sample is good to about 3 %
+    sig, E = check_model(act, through(act), loss, eb, rel=0.12)
+    inside = float((E.abs() <= sig).double().mean())
+    assert 0.62 < inside < 0.74
+    # Eq. 9 on the same loss: three quarters of the activations set to zero
+    sp, _ = make_layer(11, 16, 8, 8, 16, p_zero=0.75)
+    sig_sp, _ = check_model(sp, through(sp), loss, eb, rel=0.12)
+    R = float((sp != 0).double().mean())
+    assert sig_sp / sig == pytest.approx(math.sqrt(R), rel=0.15)
+
+
+@pytest.mark.gpu
+def test_gpu_error_model_conv_layer():
+    assert torch.cuda.is_available(), "this test needs the MI355X"
+    from paper_2011_09017_amd import binding
+    dev = torch.device("cuda", 0)
+    n, c, k, hw = 64, 64, 64, 28
+    ctx = binding.Context(sub=32, max_numel=2 * n * c * hw * hw, device=0)
+
+    def through(a, eb):
+        x = a.to(dev)
+        buf, size, rc = ctx.compress(x, eb)
+        assert rc in (binding.CMP_OK, binding.CMP_W_RANGE)
+        return ctx.decompress(buf, size, x.shape, eb).cpu()
+
+    act, loss = make_layer(5, n, c, k, hw)
+    loss_d = loss.to(dev)
+
+    def run(a, l, eb):
+        rec = through(a, eb)
+        return check_model(a.to(dev), rec.to(dev), l, eb, rel=0.03)     # 36864 gradient elements
+
+    eb = 1e-2
+    sig, E = run(act, loss_d, eb)
+    # normal: 68.2 % within one sigma, 95.4 % within two, kurtosis 3
+    inside1 = float((E.abs() <= sig).double().mean())
+    inside2 = float((E.abs() <= 2 * sig).double().mean())
+    kurt = float(((E / sig) ** 4).mean())
+    assert inside1 == pytest.approx(0.6827, abs=0.015)
+    assert inside2 == pytest.approx(0.9545, abs=0.008)
+    assert kurt == pytest.approx(3.0, abs=0.2)
+
+    # sigma is proportional to the error bound
+    sig_half, _ = run(act, loss_d, eb / 2)
+    assert sig / sig_half == pytest.approx(2.0, rel=0.04)
+
+    # twice the batch: sqrt(2) (Section 3.2)
+    act2, loss2 = make_layer(6, 2 * n, c, k, hw)
+    sig2, _ = run(act2, loss2.to(dev), eb)
+    assert sig2 / sig == pytest.approx(math.sqrt(2.0), rel=0.05)
+
+    # Eq. 9: zeros carry no error; the same loss with 75 % of the activations zero
+    sp, _ = make_layer(5, n, c, k, hw, p_zero=0.75)
+    sig_sp, _ = run(sp, loss_d, eb)
+    R = float((sp != 0).double().mean())
+    assert sig_sp / sig == pytest.approx(math.sqrt(R), rel=0.03)
+
+    # Eq. 5 with a = 0.32 and Lbar = mean over the samples of max |L|: right order of magnitude only
+    lbar = float(loss.abs().flatten(1).max(dim=1).values.mean())
+    est = 0.32 * lbar * math.sqrt(n) * eb
+    assert 0.05 < sig / est < 20.0, (sig, est)
+    # and the estimator of Sections 4.1-4.3 turned round: the bound it proposes for a target
+    # sigma yields a measured sigma within that same factor of the target
+    mom = torch.full((k, c, 3, 3), 100.0 * est, dtype=torch.float32)      # 0.01 * M_avg = est
+    rc, eb_prop, (R1, Lb, Mavg) = ctx.estimate_eb(act.to(dev), loss.float().to(dev).contiguous(), mom.to(dev))
+    assert rc == binding.CMP_OK and R1 == 1.0
+    assert eb_prop == pytest.approx(eb, rel=1e-3)
