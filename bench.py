@@ -203,21 +203,22 @@ def main() -> int:
     tc /= args.steps; td /= args.steps
 
     # ---- per-kernel durations (events around every launch), same K steps ----------------
-    # One call at a time (a device-wide wait after each), so that a kernel's duration is its own
-    # and not that of whatever another stream ran beside it.
+    # All calls on one stream, back to back: kernels of one stream run in order, so a kernel's
+    # duration is its own and not that of whatever another stream ran beside it, and no launch
+    # starts on an idle GPU (an event pair around the first kernel after a device-wide wait also
+    # times the wake-up: 10-20 us, which a rocprofv3 kernel trace does not show).
     for c in ctxs:
         c.profile(True)
     for _ in range(args.steps):
         for i in order:
             rc, _ = binding.cmp_compress(ctxs[i % K]._h, xs[i].data_ptr(), xs[i].shape, eb, arena[i].data_ptr(),
-                                         arena[i].numel(), False, streams[i % S])
+                                         arena[i].numel(), False, streams[0])
             assert rc == 0, binding.cmp_strerror(rc)
-            torch.cuda.synchronize()
         for i in reversed(order):
             rc = binding.cmp_decompress(ctxs[i % K]._h, arena[i].data_ptr(), bounds[i], xs[i].shape, eb,
-                                        outs[i].data_ptr(), streams[i % S])
+                                        outs[i].data_ptr(), streams[0])
             assert rc == 0, binding.cmp_strerror(rc)
-            torch.cuda.synchronize()
+    torch.cuda.synchronize()
     kern = {}
     for k, c in enumerate(ctxs):
         for name, (ms, launches) in c.profile_read(streams[0]).items():
