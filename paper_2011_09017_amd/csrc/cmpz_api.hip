@@ -12,7 +12,7 @@ namespace cmpz {
 const char *const kKernelNames[kKernelCount] = {
     "k_quant_lorenzo_split_hist", "k_codebook", "k_encode", "k_outliers",
     "k_empty_container", "k_decode_tables", "k_decode", "k_patch_outliers", "k_row_scan",
-    "k_col_scan_dequant", "k_decode_fused", "k_controller_stats"};
+    "k_col_scan_dequant", "k_decode_fused", "k_decode_fused_rest", "k_controller_stats"};
 }  // namespace cmpz
 
 using namespace cmpz;
@@ -28,6 +28,7 @@ struct cmp_ctx {
     uint8_t   *d_lens;
     uint64_t  *d_codes;
     void      *d_tables;
+    uint32_t  *d_items;      // item list of the fused decode kernels
     ControllerScratch *d_ctl;
     ControllerResult  *d_ctl_result;
     uint64_t   last_numel;
@@ -155,6 +156,7 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     const uint64_t o_lens = carve(kMaxSym);
     const uint64_t o_codes = carve(8 * kMaxSym);
     const uint64_t o_tables = carve(decode_tables_bytes());
+    const uint64_t o_items = carve(4 * fused_item_words(c.max_numel));
     const uint64_t o_ctl = carve(sizeof(ControllerScratch));
     const uint64_t o_ctl_result = carve(sizeof(ControllerResult));
     if (hipMalloc(reinterpret_cast<void **>(&ctx->d_base), off) != hipSuccess) { delete ctx; return CMP_E_HIP; }
@@ -172,6 +174,7 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     ctx->d_lens = ctx->d_base + o_lens;
     ctx->d_codes = reinterpret_cast<uint64_t *>(ctx->d_base + o_codes);
     ctx->d_tables = ctx->d_base + o_tables;
+    ctx->d_items = reinterpret_cast<uint32_t *>(ctx->d_base + o_items);
     ctx->d_ctl = reinterpret_cast<ControllerScratch *>(ctx->d_base + o_ctl);
     ctx->d_ctl_result = reinterpret_cast<ControllerResult *>(ctx->d_base + o_ctl_result);
     *out = ctx;
@@ -347,7 +350,7 @@ int cmp_decompress(cmp_ctx *ctx, const void *d_buf, size_t size, const int64_t s
 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
-    launch_decompress(a, ctx->d_tables, &ctx->prof, static_cast<hipStream_t>(stream));
+    launch_decompress(a, ctx->d_tables, ctx->d_items, &ctx->prof, static_cast<hipStream_t>(stream));
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
     return CMP_OK;
 }

@@ -50,7 +50,11 @@ struct FusedPlan {
     uint32_t Rb;           // rows per band (big == 1)
     uint32_t nitems;
     FastDiv  divW;
+    uint32_t use_list;     // the int32 kernel walks the listed items only (else: all items)
+    uint32_t *items;       // items[0]: number of listed items, items[1]: workgroups that are done with
+                           // the list, items[2..]: the listed items
 };
+constexpr uint32_t kItemList = 2;
 
 #ifdef CMPZ_PHASE_CLOCKS
 #define PHASE(k) if (tid == 0) { const long long now_ = clock64(); clk[k] += now_ - last_; last_ = now_; }
@@ -77,9 +81,16 @@ struct Stage {
     uint32_t nq;           // units staged; 0 = not staged (the band decodes from memory)
 };
 
-template <int SUB>
-__global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, FusedPlan pl)
+// R16 = true: the fast kernel, for sub <= 64.  Residual sums are kept as int16 (a lane's running
+// sum over at most 64 in-range residuals stays below 2^15), which makes room for four workgroups
+// per CU.  It takes the items (planes, groups of small planes) whose chunks hold no outlier and
+// puts the others on a list.  R16 = false: int32 residuals and the outlier path, for that list
+// (pl.use_list) or, for sub = 128, for every item.
+template <int SUB, bool R16>
+__global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(DecompressArgs a, FusedPlan pl)
 {
+    using RT = typename std::conditional<R16, int16_t, int32_t>::type;
+    constexpr int kRows = 8;                              // rows of the column pass in flight together
     constexpr int kLog  = Cfg<SUB>::kLog;
     constexpr int kND   = kBandMax / SUB;                 // decode lanes per band
     constexpr int kNSub = (int)kChunk / SUB;              // sub-blocks per chunk
@@ -89,7 +100,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
     static_assert(kStageWords / 4 == 2 * kWave, "two units per lane");
 
     __shared__ DecodeTables T;
-    __shared__ int32_t  Rs[kWaves][kBandMax + kND];       // one pad word per sub-block: lane-conflict free
+    __shared__ RT       Rs[kWaves][kBandMax + kND];       // one pad slot per sub-block: lane-conflict free
     __shared__ uint32_t Ps[kWaves][kE * kWave + 2];       // exclusive prefix of sub-block bit counts
     __shared__ __align__(16) uint32_t Ss[kWaves][kStagePad + kStageWords + 4];   // staged payload; after the decode, the lane records
 
@@ -99,17 +110,30 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
     long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = clock64();
 #endif
+    uint32_t n_listed = 0;
+    if (!R16 && pl.use_list) {
+        // nothing listed (the usual case): leave before the tables are built; the last workgroup
+        // to leave, or to finish, re-arms the list
+        n_listed = __hip_atomic_load(pl.items, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (n_listed == 0) {
+            if (tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) pl.items[1] = 0;
+            return;
+        }
+    }
     // every workgroup validates the container and builds the decode tables for itself
     {
         const uint32_t defect = build_tables_256(T, a, reinterpret_cast<uint32_t *>(&Rs[0][0]));
         if (defect) {
             if (blockIdx.x == 0 && tid == 0) atomicOr(a.status, defect);
+            if (!R16 && pl.use_list && tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) {
+                pl.items[0] = 0; pl.items[1] = 0;
+            }
             return;
         }
     }
     PHASE(0)
     // ---- from here on the waves are on their own ----
-    int32_t  *R = Rs[wv];
+    RT       *R = Rs[wv];
     uint32_t *P = Ps[wv];
     uint32_t *S = Ss[wv];
     // per decode lane, after the decode: .x = offset of the lane's first row start (elements before
@@ -131,7 +155,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
     // What a lane fetches ahead for a band: its bit-count entries, its sub-block's chunk bounds,
     // and (uniform) the band's range in the outlier list and the payload bounds of its chunks.
     struct Ahead {
-        uint32_t v[kE], uu0, uu1, olo, ohi, cf, cl, cl1;
+        uint32_t v[kE], uu0, uu1, olo, ohi, cf, cl, cl1, ilo, ihi;
     };
 
     const uint32_t vzero = __builtin_amdgcn_mbcnt_lo(0u, 0u);    // 0, but not known to be uniform
@@ -155,7 +179,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         Ahead f;
 #pragma unroll
         for (int i = 0; i < kE; ++i) f.v[i] = 0;
-        f.uu0 = f.uu1 = f.olo = f.ohi = f.cf = f.cl = f.cl1 = 0;
+        f.uu0 = f.uu1 = f.olo = f.ohi = f.cf = f.cl = f.cl1 = f.ilo = f.ihi = 0;
         if (!g.valid) return f;
         const uint32_t sb0 = g.e0 >> kLog, sb1 = (g.e0 + g.n - 1) >> kLog;
         const uint32_t j0 = sb0 & (kNSub - 1), ent0 = sb0 - j0, nent = j0 + (sb1 - sb0 + 1);
@@ -175,6 +199,14 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         f.cf = chunk_off[sb0 / kNSub + vzero];
         f.cl = chunk_off[sb1 / kNSub + vzero];
         f.cl1 = chunk_off[sb1 / kNSub + 1 + vzero];
+        if (R16) {
+            // outlier records of all chunks the band's item touches (for a group of small planes
+            // the band is the item)
+            const uint32_t i0 = pl.big ? g.plane0 * HW : g.e0;
+            const uint32_t i1 = pl.big ? i0 + HW - 1 : g.e0 + g.n - 1;
+            f.ilo = outl_off[i0 / kChunk + vzero];
+            f.ihi = outl_off[i1 / kChunk + 1 + vzero];
+        }
         return f;
     };
     // exclusive prefix of a band's bit counts from the start of its first chunk
@@ -216,7 +248,13 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
 
     const uint32_t nbands_big = pl.big ? (H + pl.Rb - 1) / pl.Rb : 1u;
     const uint32_t item_stride = gridDim.x * kWaves;
-    uint32_t item = blockIdx.x * kWaves + wv, b = 0;
+    // the wave's items: every item_stride-th item, or (R16 = false) every item_stride-th listed one
+    auto item_of = [&](uint32_t sl) -> uint32_t {
+        if (R16 || !pl.use_list) return sl;
+        return sl < n_listed ? pl.items[kItemList + sl] : 0xffffffffu;
+    };
+    uint32_t slot = blockIdx.x * kWaves + wv, b = 0;
+    uint32_t item = item_of(slot);
     Band cur = band_of(item, b);
     Ahead fa = fetch(cur);
     int32_t colacc[kColGroups] = {0, 0, 0, 0};               // running column sums (big planes)
@@ -230,8 +268,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
 
     while (cur.valid) {
         // ---- next band: geometry now, bit counts in flight while this band is decoded ----
-        uint32_t nitem = item, nb = b + 1;
-        if (nb >= nbands_big) { nitem = item + item_stride; nb = 0; }
+        uint32_t nslot = slot, nitem = item, nb = b + 1;
+        if (nb >= nbands_big) { nslot = slot + item_stride; nitem = item_of(nslot); nb = 0; }
         const Band nxt = band_of(nitem, nb);
         const Ahead fn = fetch(nxt);
 
@@ -266,7 +304,16 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         // outliers of the band: a range of the outlier list (filtered by index below)
         uint32_t olo = __builtin_amdgcn_readfirstlane(fa.olo), ohi = __builtin_amdgcn_readfirstlane(fa.ohi);
         if (olo > ohi || ohi > n_outl) { bad = true; olo = ohi = 0; }
-        const bool folded = (olo == ohi);                // uniform: no outliers, rows are summed while decoding
+        // uniform: no outliers, rows are summed while decoding
+        const bool folded = R16 ? true : (olo == ohi);
+        // the fast kernel leaves an item whose chunks hold outliers to the other kernel
+        bool skip = false;
+        if (R16) {
+            skip = __builtin_amdgcn_readfirstlane(fa.ilo) != __builtin_amdgcn_readfirstlane(fa.ihi);
+            if (!skip && olo != ohi) { bad = true; skip = true; }        // the two ranges disagree
+            if (skip && b == 0 && lane == 0) pl.items[kItemList + atomicAdd(pl.items, 1u)] = item;
+        }
+        if (!skip) {
 
         // ---- decode: one lane per sub-block ----
         int32_t my_tail = 0;
@@ -282,7 +329,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
             // elements of this sub-block that belong to the band: k in [klo, khi)
             const uint32_t klo = (el0 < e0) ? e0 - el0 : 0u;
             const uint32_t khi = (el0 + n_here > e0 + n) ? e0 + n - el0 : n_here;
-            int32_t *my = R + lane * (SUB + 1);
+            RT *my = R + lane * (SUB + 1);
             my_reset = klo;
             // position of the sub-block in the staging buffer (its chunk must lie in the staged stretch)
             uint32_t spos = 0;
@@ -384,6 +431,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
             }
         }
         wave_sync();
+        }   // !skip
         PHASE(4)
 
         // ---- next band: bit positions now, its payload in flight during the column pass ----
@@ -395,6 +443,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
         }
         PHASE(2)
 
+        if (!skip) {
         // ---- column prefix sums (adding the lanes' carries); wide rows are de-quantised and stored from here ----
         const bool direct = W >= 32;                     // a wave then stores runs of >= 128 bytes
         const uint32_t nrow = pl.big ? rows : H;
@@ -408,24 +457,24 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
             uint32_t u = p * HW + w + u0;
             uint32_t off = (p * HW + w) * 4u;
             uint32_t h = 0;
-            for (; h + 8 <= nrow; h += 8) {              // 8 rows at a time: loads in flight together
-                int32_t t8[8];
-                uint32_t ph[8], kk[8];
-                uint2 rc[8];
+            for (; h + kRows <= nrow; h += kRows) {      // kRows rows at a time: loads in flight together
+                int32_t t8[kRows];
+                uint32_t ph[kRows], kk[kRows];
+                uint2 rc[kRows];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
+                for (int q = 0; q < kRows; ++q) {
                     const uint32_t uq = u + q * W, t = uq >> kLog;
                     ph[q] = uq + t; kk[q] = uq & (uint32_t)(SUB - 1);
                     t8[q] = R[ph[q]]; rc[q] = RC[t];
                 }
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
+                for (int q = 0; q < kRows; ++q) {
                     acc += t8[q] + ((kk[q] < rc[q].x) ? (int32_t)rc[q].y : 0);
                     if (kDirect) *reinterpret_cast<float *>(band_out + (off + q * 4u * W)) = (float)acc * s;
                     else R[ph[q]] = acc;
                 }
-                u += 8 * W;
-                off += 32u * W;
+                u += kRows * W;
+                off += 4u * kRows * W;
             }
             for (; h < nrow; ++h, u += W, off += 4u * W) {
                 const uint32_t t = u >> kLog, ph = u + t;
@@ -472,11 +521,17 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
                 }
             }
         }
+        }   // !skip
         wave_sync();                                      // R and the staging buffer are reused by the next band
         PHASE(5)
-        cur = nxt; fa = fn; sg = sgn; item = nitem; b = nb;
+        cur = nxt; fa = fn; sg = sgn; item = nitem; slot = nslot; b = nb;
     }
     if (bad) atomicOr(a.status, kStFormat);
+    if (!R16 && pl.use_list) {
+        // the last workgroup to finish re-arms the list for the next call
+        __syncthreads();
+        if (tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) { pl.items[0] = 0; pl.items[1] = 0; }
+    }
 #ifdef CMPZ_PHASE_CLOCKS
     if (tid == 0)
         for (int k = 0; k < 8; ++k)
@@ -487,12 +542,14 @@ __global__ __launch_bounds__(kThreads, 3) void k_decode_fused(DecompressArgs a, 
 }  // namespace
 
 // Returns false when the shape does not fit the fused kernel (caller falls back).
-bool launch_decode_fused(const DecompressArgs &a, Profiler *prof, hipStream_t st)
+// `items` is scratch of fused_item_words(numel) 32-bit words, zero before the first call.
+bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, Profiler *prof, hipStream_t st)
 {
     const uint32_t ndec = kBandMax / a.sub;
     const uint64_t cap = (uint64_t)(ndec - 1) * a.sub + 1;     // a band then spans at most ndec sub-blocks
     FusedPlan pl;
     pl.divW = FastDiv::make(a.W);
+    pl.items = items;
     if (a.HW <= cap) {
         pl.big = 0; pl.G = (uint32_t)(cap / a.HW); pl.Rb = 0;
         pl.nitems = (a.planes + pl.G - 1) / pl.G;
@@ -504,13 +561,30 @@ bool launch_decode_fused(const DecompressArgs &a, Profiler *prof, hipStream_t st
     }
     // every workgroup builds the decode tables once and then loops: no more workgroups than fit the chip
     const uint32_t want = (pl.nitems + kWaves - 1) / kWaves;
-    const uint32_t grid = want < 256u * 3u ? want : 256u * 3u;
+    const uint32_t grid4 = want < 256u * 4u ? want : 256u * 4u;
+    const uint32_t grid3 = want < 256u * 3u ? want : 256u * 3u;
+    const uint32_t grid1 = want < 256u ? want : 256u;
     switch (a.sub) {
-    case 32:  launch(prof, kKDecodeFused, k_decode_fused<32>, dim3(grid), dim3(kThreads), st, a, pl); break;
-    case 64:  launch(prof, kKDecodeFused, k_decode_fused<64>, dim3(grid), dim3(kThreads), st, a, pl); break;
-    default:  launch(prof, kKDecodeFused, k_decode_fused<128>, dim3(grid), dim3(kThreads), st, a, pl); break;
+    case 32:
+        pl.use_list = 1;
+        launch(prof, kKDecodeFused, k_decode_fused<32, true>, dim3(grid4), dim3(kThreads), st, a, pl);
+        launch(prof, kKDecodeFusedRest, k_decode_fused<32, false>, dim3(grid1), dim3(kThreads), st, a, pl);
+        break;
+    case 64:
+        pl.use_list = 1;
+        launch(prof, kKDecodeFused, k_decode_fused<64, true>, dim3(grid4), dim3(kThreads), st, a, pl);
+        launch(prof, kKDecodeFusedRest, k_decode_fused<64, false>, dim3(grid1), dim3(kThreads), st, a, pl);
+        break;
+    default:
+        pl.use_list = 0;
+        launch(prof, kKDecodeFused, k_decode_fused<128, false>, dim3(grid3), dim3(kThreads), st, a, pl);
+        break;
     }
     return true;
 }
+
+// Words of scratch the item list of a tensor of `numel` elements can need: an item is a whole
+// plane of more than 1921 elements or a group of planes with more than 960 elements together.
+uint64_t fused_item_words(uint64_t numel) { return kItemList + numel / 900 + 64; }
 
 }  // namespace cmpz

@@ -196,7 +196,7 @@ __device__ __forceinline__ uint32_t rank_within_length(uint32_t L, uint32_t (*wa
 // Kernel identifiers for the optional per-kernel timing (cmp_profile).
 enum KernelId : int {
     kKQuantLorenzoHist = 0, kKCodebook, kKEncode, kKOutliers, kKEmpty,
-    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKControllerStats,
+    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKDecodeFusedRest, kKControllerStats,
     kKernelCount
 };
 extern const char *const kKernelNames[kKernelCount];
@@ -234,8 +234,9 @@ void launch_compress_finish(const CompressArgs &a, Profiler *prof, hipStream_t s
 void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st);
 bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st);
 size_t decode_tables_bytes();
-void launch_decompress(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st);
-bool launch_decode_fused(const DecompressArgs &a, Profiler *prof, hipStream_t st);
+void launch_decompress(const DecompressArgs &a, void *tables, uint32_t *items, Profiler *prof, hipStream_t st);
+bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, Profiler *prof, hipStream_t st);
+uint64_t fused_item_words(uint64_t numel);
 
 // Error-bound estimator: device scratch (zero between calls) and result record.
 constexpr uint32_t kMaxBatch = 65536;
