@@ -115,6 +115,29 @@ def test_band_and_group_shapes(gpu, orc, sub, shape):
     check_case(gpu, orc, x, 1e-2, ctx, orc.Config(sub=sub))
 
 
+@pytest.mark.parametrize("sub", [32, 64])
+def test_items_with_and_without_outliers(gpu, orc, sub):
+    """The fast decode kernel hands the planes (or groups of small planes) whose chunks hold
+    outliers to the second kernel: planes of both kinds side by side, many listed items, none, and
+    the same context again afterwards (the list must be empty again)."""
+    ctx = make_ctx(gpu, sub=sub)
+    ocfg = orc.Config(sub=sub)
+    rng = np.random.default_rng(7 + sub)
+    for shape in [(4, 8, 56, 56), (6, 40, 14, 14), (3, 5, 120, 100)]:
+        x = activation(shape, 5, 0.5, seed=11 * sub + shape[2]).numpy()
+        n, c = shape[0], shape[1]
+        for _ in range(max(2, n * c // 5)):                  # spikes in about a fifth of the planes
+            x[rng.integers(n), rng.integers(c), rng.integers(shape[2]), rng.integers(shape[3])] = 300.0
+        h = check_case(gpu, orc, x, 1e-2, ctx, ocfg)
+        assert h["n_outliers"] > 0
+        y = activation(shape, 5, 0.5, seed=13 * sub + shape[2]).numpy()      # no outliers at all
+        h = check_case(gpu, orc, y, 1e-2, ctx, ocfg)
+        assert h["n_outliers"] == 0
+        x[:] = 300.0 * (rng.random(shape) < 0.02)            # outliers everywhere
+        h = check_case(gpu, orc, x.astype(np.float32), 1e-2, ctx, ocfg)
+        assert h["n_outliers"] > 0
+
+
 def test_all_zero_constant_and_single_symbol(gpu, orc):
     ctx = make_ctx(gpu)
     x = np.zeros((2, 2, 30, 30), np.float32)
