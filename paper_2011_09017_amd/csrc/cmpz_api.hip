@@ -29,6 +29,8 @@ struct cmp_ctx {
     uint64_t  *d_codes;
     void      *d_tables;
     uint32_t  *d_items;      // item list of the fused decode kernels
+    uint32_t  *h_hint;       // pinned host word the decode kernels report to (see launch_decode_fused)
+    uint32_t  *d_hint;       // its device address
     ControllerScratch *d_ctl;
     ControllerResult  *d_ctl_result;
     uint64_t   last_numel;
@@ -175,6 +177,13 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     ctx->d_codes = reinterpret_cast<uint64_t *>(ctx->d_base + o_codes);
     ctx->d_tables = ctx->d_base + o_tables;
     ctx->d_items = reinterpret_cast<uint32_t *>(ctx->d_base + o_items);
+    ctx->h_hint = nullptr; ctx->d_hint = nullptr;
+    if (hipHostMalloc(reinterpret_cast<void **>(&ctx->h_hint), 64, hipHostMallocMapped) != hipSuccess ||
+        hipHostGetDevicePointer(reinterpret_cast<void **>(&ctx->d_hint), ctx->h_hint, 0) != hipSuccess) {
+        if (ctx->h_hint) (void)hipHostFree(ctx->h_hint);
+        (void)hipFree(ctx->d_base); delete ctx; return CMP_E_HIP;
+    }
+    *ctx->h_hint = 1;                                  // nothing known yet: assume listed items
     ctx->d_ctl = reinterpret_cast<ControllerScratch *>(ctx->d_base + o_ctl);
     ctx->d_ctl_result = reinterpret_cast<ControllerResult *>(ctx->d_base + o_ctl_result);
     *out = ctx;
@@ -187,6 +196,7 @@ void cmp_destroy(cmp_ctx *ctx)
     DeviceGuard guard(ctx->device);
     (void)hipDeviceSynchronize();
     for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
+    if (ctx->h_hint) (void)hipHostFree(ctx->h_hint);
     (void)hipFree(ctx->d_base);
     delete ctx;
 }
@@ -350,7 +360,8 @@ int cmp_decompress(cmp_ctx *ctx, const void *d_buf, size_t size, const int64_t s
 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
-    launch_decompress(a, ctx->d_tables, ctx->d_items, &ctx->prof, static_cast<hipStream_t>(stream));
+    launch_decompress(a, ctx->d_tables, ctx->d_items, ctx->h_hint, ctx->d_hint, &ctx->prof,
+                      static_cast<hipStream_t>(stream));
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
     return CMP_OK;
 }

@@ -51,6 +51,7 @@ struct FusedPlan {
     uint32_t nitems;
     FastDiv  divW;
     uint32_t use_list;     // the int32 kernel walks the listed items only (else: all items)
+    uint32_t *listed_hint; // host-visible word: how many items the latest finished call had listed
     uint32_t *items;       // items[0]: number of listed items, items[1]: workgroups that are done with
                            // the list, items[2..]: the listed items
 };
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
         // to leave, or to finish, re-arms the list
         n_listed = __hip_atomic_load(pl.items, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (n_listed == 0) {
-            if (tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) pl.items[1] = 0;
+            if (tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) { pl.items[1] = 0; *pl.listed_hint = 0; }
             return;
         }
     }
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
         if (defect) {
             if (blockIdx.x == 0 && tid == 0) atomicOr(a.status, defect);
             if (!R16 && pl.use_list && tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) {
-                pl.items[0] = 0; pl.items[1] = 0;
+                pl.items[0] = 0; pl.items[1] = 0; *pl.listed_hint = n_listed;
             }
             return;
         }
@@ -530,7 +531,9 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
     if (!R16 && pl.use_list) {
         // the last workgroup to finish re-arms the list for the next call
         __syncthreads();
-        if (tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) { pl.items[0] = 0; pl.items[1] = 0; }
+        if (tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) {
+            pl.items[0] = 0; pl.items[1] = 0; *pl.listed_hint = n_listed;
+        }
     }
 #ifdef CMPZ_PHASE_CLOCKS
     if (tid == 0)
@@ -543,13 +546,19 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
 
 // Returns false when the shape does not fit the fused kernel (caller falls back).
 // `items` is scratch of fused_item_words(numel) 32-bit words, zero before the first call.
-bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, Profiler *prof, hipStream_t st)
+// `hint_host` / `hint_dev`: one word of pinned host memory and its device address.  The kernel
+// for the listed items leaves there how many it found; the next call sizes that kernel's grid by
+// it (a small grid is scheduled and gone quickly when, as usual, nothing is listed).  The word
+// is only a hint: whatever the grid, the kernel works through the whole list.
+bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, const volatile uint32_t *hint_host,
+                         uint32_t *hint_dev, Profiler *prof, hipStream_t st)
 {
     const uint32_t ndec = kBandMax / a.sub;
     const uint64_t cap = (uint64_t)(ndec - 1) * a.sub + 1;     // a band then spans at most ndec sub-blocks
     FusedPlan pl;
     pl.divW = FastDiv::make(a.W);
     pl.items = items;
+    pl.listed_hint = hint_dev;
     if (a.HW <= cap) {
         pl.big = 0; pl.G = (uint32_t)(cap / a.HW); pl.Rb = 0;
         pl.nitems = (a.planes + pl.G - 1) / pl.G;
@@ -563,7 +572,8 @@ bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, Profiler *pro
     const uint32_t want = (pl.nitems + kWaves - 1) / kWaves;
     const uint32_t grid4 = want < 256u * 4u ? want : 256u * 4u;
     const uint32_t grid3 = want < 256u * 3u ? want : 256u * 3u;
-    const uint32_t grid1 = want < 256u ? want : 256u;
+    const uint32_t rest_max = (*hint_host == 0) ? 32u : 256u;
+    const uint32_t grid1 = want < rest_max ? want : rest_max;
     switch (a.sub) {
     case 32:
         pl.use_list = 1;

@@ -287,9 +287,10 @@ __global__ __launch_bounds__(kThreads) void k_col_scan_dequant(DecompressArgs a)
 
 size_t decode_tables_bytes() { return sizeof(DecodeTables); }
 
-void launch_decompress(const DecompressArgs &a, void *tables, uint32_t *items, Profiler *prof, hipStream_t st)
+void launch_decompress(const DecompressArgs &a, void *tables, uint32_t *items, const volatile uint32_t *hint_host,
+                       uint32_t *hint_dev, Profiler *prof, hipStream_t st)
 {
-    if (a.numel != 0 && launch_decode_fused(a, items, prof, st)) return;
+    if (a.numel != 0 && launch_decode_fused(a, items, hint_host, hint_dev, prof, st)) return;
     DecodeTables *tb = static_cast<DecodeTables *>(tables);
     launch(prof, kKDecodeTables, k_decode_tables, dim3(1), dim3(1024), st, a, tb);
     if (a.numel == 0) return;

@@ -234,8 +234,10 @@ void launch_compress_finish(const CompressArgs &a, Profiler *prof, hipStream_t s
 void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st);
 bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st);
 size_t decode_tables_bytes();
-void launch_decompress(const DecompressArgs &a, void *tables, uint32_t *items, Profiler *prof, hipStream_t st);
-bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, Profiler *prof, hipStream_t st);
+void launch_decompress(const DecompressArgs &a, void *tables, uint32_t *items, const volatile uint32_t *hint_host,
+                       uint32_t *hint_dev, Profiler *prof, hipStream_t st);
+bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, const volatile uint32_t *hint_host,
+                         uint32_t *hint_dev, Profiler *prof, hipStream_t st);
 uint64_t fused_item_words(uint64_t numel);
 
 // Error-bound estimator: device scratch (zero between calls) and result record.
