@@ -185,7 +185,7 @@ bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st)
     pl.divHW = FastDiv::make(a.HW);
     // every workgroup ends with a flush of its histogram (contended atomics): few, long-lived
     // workgroups, but still a few per CU
-    pl.chunks_per_wg = (a.lay.nchunks + 1535) / 1536;
+    pl.chunks_per_wg = (a.lay.nchunks + 2047) / 2048;
     if (pl.chunks_per_wg < 1) pl.chunks_per_wg = 1;
     const uint32_t grid = (a.lay.nchunks + pl.chunks_per_wg - 1) / pl.chunks_per_wg;
     launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist_tiled, dim3(grid), dim3(kThreads), st, a, pl);
