@@ -14,7 +14,8 @@
 //
 // A band is decoded by one lane per sub-block (the container stores each
 // sub-block's bit count, so every lane knows where its codes start) into an LDS
-// array of int32.  The band's stretch of the payload is contiguous in the
+// array (int16 in the fast instance of the kernel, int32 in the other: see
+// k_decode_fused).  The band's stretch of the payload is contiguous in the
 // container; it is copied into LDS with 128-bit loads first, and the lanes read
 // their codewords from there at arbitrary bit positions (a band whose payload
 // exceeds the staging buffer, more than 8 bits per code on average, is decoded
