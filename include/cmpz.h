@@ -88,7 +88,9 @@ typedef struct {
 void cmp_default_config(cmp_config *cfg);
 
 /* Create a context on GPU `device` and allocate its scratch (about
- * 2 bytes * max_numel + 16 bytes per chunk).  cfg == NULL means defaults. */
+ * 2 bytes * max_numel + 16 bytes per chunk of device memory, and 64 bytes of
+ * pinned host memory that the decompression kernels report to).  cfg == NULL
+ * means defaults. */
 int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device);
 void cmp_destroy(cmp_ctx *ctx);
 
