@@ -20,7 +20,7 @@
  *  - All work of one context must be issued on one stream at a time; calls on
  *    one context are not re-entrant.  Use one context per concurrent stream.
  *  - Tensors are fp32, contiguous NCHW; d_x, d_xout and d_out must be 16-byte
- *    aligned.  numel must be below 2^32.  A dimension may be 0 (empty tensor).
+ *    aligned.  numel must not exceed 2^32 - 8192.  A dimension may be 0 (empty tensor).
  *  - Return value: 0 = CMP_OK, negative = error, positive = warning.
  *    Conditions only the GPU can see (container too small, malformed container,
  *    out-of-range input) are recorded on the device and reported by the next
@@ -64,7 +64,7 @@ extern "C" {
 #endif
 
 #define CMP_OK           0
-#define CMP_E_ARG      (-1)  /* NULL pointer, bad shape, numel >= 2^32 or > max_numel, eb not
+#define CMP_E_ARG      (-1)  /* NULL pointer, bad shape, numel > 2^32 - 8192 or > max_numel, eb not
                                 finite or outside [2^-60, 2^60], unsupported configuration   */
 #define CMP_E_NOSPACE  (-2)  /* out_cap smaller than the container; nothing is written past
                                 out_cap and header.status is set when the header fits        */
@@ -179,7 +179,7 @@ int cmp_profile_read(cmp_ctx *ctx, void *stream, int cap, const char **h_names,
  * eb = sigma / (a * Lbar * sqrt(batch_n * R)) (Eq. 8 with the sqrt(R) of Eq. 9), rounded once to
  * fp32 and clamped to [eb_min, eb_max].  Waits for `stream`, then stores the bound in *h_eb and,
  * if h_stats != NULL, R, Lbar, Mavg in h_stats[0..2].  The pointers must be 16-byte aligned, the
- * arrays non-empty, each shorter than 2^32 values, batch_n <= 65536.
+ * arrays non-empty, each of at most 2^32 - 8192 values, batch_n <= 65536.
  * Returns CMP_W_RANGE and eb_min when there is nothing to estimate from (no non-zero activation,
  * zero loss, NaN or infinity in a statistic); CMP_E_ARG on bad arguments. */
 typedef struct {

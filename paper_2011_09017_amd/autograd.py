@@ -144,6 +144,11 @@ class ActivationCompressor:
     def unpack(self, p):
         if not isinstance(p, _Packed):
             return p
+        if p.users <= 0:
+            # the arena block went back when the last saving node took its tensor: a second
+            # backward over the same graph would read whatever was packed there since
+            raise RuntimeError("compressed activation already released: a graph whose saved tensors "
+                               "were compressed can be walked backward once")
         if p.restored is None:
             buf = self.buffer[p.offset:p.offset + p.size]
             p.restored = self.ctx.decompress(buf, p.size, p.shape, p.eb)

@@ -85,3 +85,21 @@ def test_hooks_compress_conv_inputs_and_restore_the_oracle_reconstruction(orc):
     for g, r in zip(got, ref):
         assert torch.isfinite(g).all()
         assert (g - r).abs().max() <= 0.05 * r.abs().max() + 1e-6
+
+
+@pytest.mark.gpu
+def test_second_backward_over_released_activations_is_refused():
+    """retain_graph=True keeps the graph, but the arena blocks went back during the first backward
+    pass: the hook must refuse to decompress whatever lies there now."""
+    from paper_2011_09017_amd.autograd import ActivationCompressor
+    dev = torch.device("cuda", 0)
+    conv = torch.nn.Conv2d(4, 4, 3, padding=1).to(dev)
+    x = torch.randn(2, 4, 64, 64, device=dev).relu_()
+    comp = ActivationCompressor(1e-2, arena_bytes=4 << 20, max_numel=1 << 20, min_numel=1 << 12)
+    comp.skip_parameters(conv.parameters())
+    with comp.hooks():
+        loss = conv(x).square().mean()
+    loss.backward(retain_graph=True)
+    assert comp.stats["packed"] >= 1 and comp.arena.top == 0
+    with pytest.raises(RuntimeError, match="already released"):
+        loss.backward()

@@ -102,7 +102,7 @@ def test_oracle_error_model_small_layer():
 
 
 @pytest.mark.gpu
-def test_gpu_error_model_conv_layer():
+def test_gpu_error_model_conv_layer(orc):
     assert torch.cuda.is_available(), "this test needs the MI355X"
     from paper_2011_09017_amd import binding
     dev = torch.device("cuda", 0)
@@ -113,7 +113,13 @@ def test_gpu_error_model_conv_layer():
         x = a.to(dev)
         buf, size, rc = ctx.compress(x, eb)
         assert rc in (binding.CMP_OK, binding.CMP_W_RANGE)
-        return ctx.decompress(buf, size, x.shape, eb).cpu()
+        rec = ctx.decompress(buf, size, x.shape, eb).cpu()
+        # the statistics below are those of the oracle's reconstruction: the same bits
+        rc, obuf, osize, _ = orc.compress(a.numpy(), eb, orc.Config(sub=32))
+        assert rc >= 0 and osize == size
+        rc, oy = orc.decompress(obuf, a.shape, eb, orc.Config(sub=32))
+        assert rc == 0 and np.array_equal(rec.numpy().view(np.uint32), oy.view(np.uint32))
+        return rec
 
     act, loss = make_layer(5, n, c, k, hw)
     loss_d = loss.to(dev)

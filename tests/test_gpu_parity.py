@@ -261,9 +261,32 @@ def test_corrupted_containers_are_rejected(gpu, orc):
         bad[h[sect] + int(rng.integers(0, 8))] ^= 0x10
         ctx.decompress(bad, size, shape, 1e-2)
         ctx.last_status()
+    # a chunk whose bit stream is empty although it holds codes: header and tables consistent
+    # with a payload of zero units
+    for sub in (32, 128):
+        c2 = make_ctx(gpu, sub=sub)
+        b2, s2, _ = c2.compress(x, 1e-2)
+        g2 = b2[:s2].cpu().numpy().copy()
+        h2 = orc.parse_header(g2)
+        assert h2["n_outliers"] > 0 and h2["nchunks"] == 1
+        empty = g2[:h2["off_payload"]].copy()
+        empty[h2["off_chunk_off"] + 4:h2["off_chunk_off"] + 8] = 0                 # chunk_off[1] = 0
+        empty[h2["off_outl_off"] + 4:h2["off_outl_off"] + 8] = 0                   # no outliers either
+        empty[h2["off_sub_bits"]:h2["off_payload"]] = 0
+        empty[orc.HDR["n_outliers"]:orc.HDR["n_outliers"] + 4] = 0
+        for f in ("off_outl_idx", "off_outl_val", "total_size"):
+            empty[orc.HDR[f]:orc.HDR[f] + 8] = np.frombuffer(np.uint64(h2["off_payload"]).tobytes(), np.uint8)
+        eb2 = torch.from_numpy(np.concatenate([empty, np.zeros(4096, np.uint8)])).cuda()
+        c2.decompress(eb2, empty.size, shape, 1e-2)
+        assert c2.last_status() == gpu.CMP_E_FORMAT
     y = ctx.decompress(good, size, shape, 1e-2)
     assert ctx.last_status() == 0
     assert np.abs(y.cpu().numpy() - xh).max() <= 1e-2
+    # sizes the 32-bit indexing of the kernels cannot take are refused on the host
+    assert ctx.bound((1, 1, 65536, 65536)) == 0 and ctx.bound((1, 1, 1, (1 << 32) - 8191)) == 0
+    assert ctx.bound((1, 1, 1, (1 << 32) - 8192)) > 0
+    with pytest.raises(gpu.CmpError):
+        gpu.Context(max_numel=(1 << 32) - 8191)
 
 
 def test_determinism_and_context_reuse(gpu, orc):
@@ -316,25 +339,50 @@ def test_compress_in_two_calls_on_two_streams(gpu, orc):
     check_case(gpu, orc, x.cpu().numpy(), eb, ctx, orc.Config())
 
 
-@pytest.mark.parametrize("name,ti", FULL)
-def test_full_size_configs_bit_exact(gpu, orc, name, ti):
-    """BASELINE configs 2-4 at full size: whole container and whole reconstruction, byte for byte."""
-    wl = WORKLOADS[name]
-    ctx = make_ctx(gpu, max_numel=wl.numel())
-    x = wl.tensor(ti, device="cuda")
+def full_size_case(gpu, orc, ctx, x, eb, sub, label):
+    """Whole container and whole reconstruction of one device tensor against the oracle."""
     xh = x.cpu().numpy()
+    ocfg = orc.Config(sub=sub)
+    print(f"[parity] {label} eb={eb} sub={sub} numel={xh.size}", flush=True)
+    buf, size, rc = ctx.compress(x, eb)
+    assert rc == 0
+    orc_rc, obuf, osize, _ = orc.compress(xh, eb, ocfg)
+    assert orc_rc == 0 and size == osize
+    assert np.array_equal(buf[:size].cpu().numpy(), obuf)
+    y = ctx.decompress(buf, size, x.shape, eb)
+    assert ctx.last_status() == 0
+    yh = y.cpu().numpy()
+    orc_rc, oy = orc.decompress(obuf, xh.shape, eb, ocfg)
+    assert orc_rc == 0 and np.array_equal(yh.view(np.uint32), oy.view(np.uint32))
+    assert np.abs(yh.astype(np.float64) - xh.astype(np.float64)).max() <= float(np.float32(eb))
+    assert np.all(yh[xh == 0].view(np.uint32) == 0)
+    print(f"[parity] ok ratio={xh.nbytes / size:.3f}", flush=True)
+
+
+@pytest.mark.parametrize("sub", [32, 128])
+@pytest.mark.parametrize("name,ti", FULL)
+def test_full_size_configs_bit_exact(gpu, orc, name, ti, sub):
+    """BASELINE configs 2-4 at full size: whole container and whole reconstruction, byte for byte,
+    with the sub-block size the benchmark uses (32) and the library default (128)."""
+    wl = WORKLOADS[name]
+    ctx = make_ctx(gpu, max_numel=wl.numel(), sub=sub)
+    x = wl.tensor(ti, device="cuda")
     for eb in wl.ebs:
-        print(f"[parity] {name} eb={eb} numel={xh.size}", flush=True)
-        buf, size, rc = ctx.compress(x, eb)
-        assert rc == 0
-        orc_rc, obuf, osize, _ = orc.compress(xh, eb)
-        assert orc_rc == 0 and size == osize
-        assert np.array_equal(buf[:size].cpu().numpy(), obuf)
-        y = ctx.decompress(buf, size, x.shape, eb)
-        assert ctx.last_status() == 0
-        yh = y.cpu().numpy()
-        orc_rc, oy = orc.decompress(obuf, xh.shape, eb)
-        assert orc_rc == 0 and np.array_equal(yh.view(np.uint32), oy.view(np.uint32))
-        assert np.abs(yh.astype(np.float64) - xh.astype(np.float64)).max() <= float(np.float32(eb))
-        assert np.all(yh[xh == 0].view(np.uint32) == 0)
-        print(f"[parity] ok ratio={xh.nbytes / size:.3f}", flush=True)
+        full_size_case(gpu, orc, ctx, x, eb, sub, name)
+
+
+# config 5 (the benchmarked one): one tensor of each of its five distinct shapes, at batch 256
+CFG5_DISTINCT = [0, 1, 5, 9, 13]
+
+
+@pytest.mark.parametrize("ti", CFG5_DISTINCT)
+@pytest.mark.parametrize("name", ["cfg5_resnet18_stream", "cfg5_resnet18_stream_sparse"])
+def test_config5_shapes_full_size_bit_exact(gpu, orc, name, ti):
+    """The ResNet-18 stream at batch 256, 50 % and 85 % zeros, in the launch configuration the
+    benchmark times (sub = 32, context sized for the tensor)."""
+    wl = WORKLOADS[name]
+    shape = wl.shapes[ti]
+    n = shape[0] * shape[1] * shape[2] * shape[3]
+    ctx = make_ctx(gpu, max_numel=n, sub=32)
+    x = wl.tensor(ti, device="cuda")
+    full_size_case(gpu, orc, ctx, x, wl.ebs[0], 32, f"{name}[{ti}] {shape}")
