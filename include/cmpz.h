@@ -109,6 +109,19 @@ size_t cmp_bound(const cmp_ctx *ctx, const int64_t shape[4]);
 int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb,
                  void *d_out, size_t out_cap, size_t *h_size, void *stream);
 
+/* cmp_compress for n tensors at once (the activations of several layers, Section 4.4): every
+ * stage is ONE kernel launch over all of them (the codebooks are built side by side, one
+ * workgroup each), so that small tensors cost their bytes and not a chain of launches.  All
+ * arrays are HOST arrays of n entries: device pointers d_x[i], d_out[i], shapes[i], error bounds
+ * eb[i], capacities out_cap[i].  Container i is byte for byte what cmp_compress gives for tensor i.
+ * Calls with more than 24 tensors or more than cfg.max_numel elements in total are worked off in
+ * several groups, one after the other on `stream`; no single tensor may exceed cfg.max_numel.
+ * h_sizes == NULL: fully asynchronous.  Otherwise waits for the stream and stores the n container
+ * sizes; the return value is then the most severe per-tensor result (as for cmp_compress).
+ * Arguments are checked for all tensors before anything is launched. */
+int cmp_compress_batch(cmp_ctx *ctx, int n, const float *const *d_x, const int64_t (*shapes)[4], const float *eb,
+                       void *const *d_out, const size_t *out_cap, size_t *h_sizes, void *stream);
+
 /* cmp_compress in two calls, for callers that pipeline tensors over several streams: the single
  * workgroup that builds the Huffman codebook leaves the GPU idle, and with begin(i+1) issued on
  * one stream while finish(i) runs on another the first sweep of the next tensor fills that time.
@@ -153,7 +166,9 @@ int cmp_last_status(cmp_ctx *ctx, void *stream);
 #define CMP_STAGE_HIST        1   /* uint32[2*radius]: occurrences of each symbol              */
 #define CMP_STAGE_LENS        2   /* uint8[2*radius]: Huffman code length, 0 = unused          */
 #define CMP_STAGE_CODES       3   /* uint64[2*radius]: length << 56 | canonical code           */
-#define CMP_STAGE_COUNTERS    4   /* uint32[64]: the context's control words (diagnostics only) */
+#define CMP_STAGE_OUTLIER_IDX 4   /* uint32[n_outliers]: linear index of every outlier, ascending; this and the
+                                     next stage point into the container and wait for the GPU          */
+#define CMP_STAGE_OUTLIER_VAL 5   /* int32[n_outliers]: their Lorenzo residuals                        */
 int cmp_debug_stage(cmp_ctx *ctx, int which, const void **d_ptr, size_t *bytes);
 
 /* Per-kernel timing for benchmarks.  cmp_profile(ctx, 1) clears the record and makes

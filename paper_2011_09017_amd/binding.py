@@ -17,12 +17,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcmpz.so")
 
 CMP_OK, CMP_E_ARG, CMP_E_NOSPACE, CMP_E_FORMAT, CMP_E_MISMATCH, CMP_E_HIP, CMP_W_RANGE = 0, -1, -2, -3, -4, -5, 1
-CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES, CMP_STAGE_COUNTERS = 0, 1, 2, 3, 4
+CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES = 0, 1, 2, 3
+CMP_STAGE_OUTLIER_IDX, CMP_STAGE_OUTLIER_VAL = 4, 5
 
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
            "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",
            "cmp_profile", "cmp_profile_read", "cmp_default_controller_config", "cmp_estimate_eb",
-           "cmp_compress_begin", "cmp_compress_finish"]
+           "cmp_compress_begin", "cmp_compress_finish", "cmp_compress_batch"]
 
 
 class cmp_controller_config(C.Structure):
@@ -57,6 +58,7 @@ def lib() -> C.CDLL:
         L.cmp_last_status.argtypes = [vp, vp]; L.cmp_last_status.restype = i32
         L.cmp_debug_stage.argtypes = [vp, i32, vp, vp]; L.cmp_debug_stage.restype = i32
         L.cmp_strerror.argtypes = [i32]; L.cmp_strerror.restype = C.c_char_p
+        L.cmp_compress_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]; L.cmp_compress_batch.restype = i32
         L.cmp_compress_begin.argtypes = [vp, vp, vp, C.c_float, vp]; L.cmp_compress_begin.restype = i32
         L.cmp_compress_finish.argtypes = [vp, vp, sz, vp, vp]; L.cmp_compress_finish.restype = i32
         L.cmp_default_controller_config.argtypes = [vp]; L.cmp_default_controller_config.restype = None
@@ -101,6 +103,20 @@ def cmp_compress(ctx, d_x: int, shape, eb: float, d_out: int, out_cap: int, want
     rc = lib().cmp_compress(ctx, d_x, C.addressof(s), C.c_float(eb), d_out, out_cap,
                             C.addressof(size) if want_size else None, stream)
     return rc, int(size.value)
+
+
+def cmp_compress_batch(ctx, d_xs, shapes, ebs, d_outs, out_caps, want_sizes: bool, stream: int):
+    """Lists of raw device pointers / shapes / error bounds / capacities.  Returns (rc, sizes or None)."""
+    n = len(d_xs)
+    assert len(shapes) == n and len(ebs) == n and len(d_outs) == n and len(out_caps) == n
+    xs = (C.c_void_p * n)(*d_xs)
+    outs = (C.c_void_p * n)(*d_outs)
+    sh = (C.c_int64 * (4 * n))(*[int(v) for s in shapes for v in s])
+    eb = (C.c_float * n)(*ebs)
+    caps = (C.c_size_t * n)(*out_caps)
+    sizes = (C.c_size_t * n)()
+    rc = lib().cmp_compress_batch(ctx, n, xs, sh, eb, outs, caps, sizes if want_sizes else None, stream)
+    return rc, ([int(v) for v in sizes] if want_sizes else None)
 
 
 def cmp_compressed_size(ctx, d_buf: int, stream: int):
@@ -208,6 +224,18 @@ class Context:
         if rc < 0 and rc != CMP_E_NOSPACE:
             raise CmpError(rc, "cmp_compress")
         return out, (size if sync else None), rc
+
+    def compress_batch(self, xs, ebs, outs=None, sync: bool = True):
+        """Several tensors in one call.  Returns (containers, sizes or None, rc)."""
+        for x in xs:
+            assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 4
+        if outs is None:
+            outs = [torch.empty(self.bound(x.shape), dtype=torch.uint8, device=x.device) for x in xs]
+        rc, sizes = cmp_compress_batch(self._h, [x.data_ptr() for x in xs], [x.shape for x in xs], list(ebs),
+                                       [o.data_ptr() for o in outs], [o.numel() for o in outs], sync, self._stream())
+        if rc < 0 and rc != CMP_E_NOSPACE:
+            raise CmpError(rc, "cmp_compress_batch")
+        return outs, sizes, rc
 
     def compressed_size(self, buf: torch.Tensor):
         return cmp_compressed_size(self._h, buf.data_ptr(), self._stream())

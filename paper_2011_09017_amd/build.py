@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcmpz.so")
-SOURCES = ["cmpz_api.hip", "cmpz_compress.hip", "cmpz_sweep1.hip", "cmpz_codebook.hip", "cmpz_decompress.hip", "cmpz_decode_fused.hip",
+SOURCES = ["cmpz_api.hip", "cmpz_compress.hip", "cmpz_sweep1.hip", "cmpz_codebook.hip", "cmpz_pack.hip", "cmpz_decompress.hip", "cmpz_decode_fused.hip",
            "cmpz_controller.hip"]
 
 # -ffp-contract=off: the quantiser multiplies must stay single roundings (no FMA).

@@ -10,31 +10,41 @@
 
 namespace cmpz {
 const char *const kKernelNames[kKernelCount] = {
-    "k_quant_lorenzo_split_hist", "k_codebook", "k_encode", "k_outliers",
-    "k_empty_container", "k_decode_tables", "k_decode", "k_patch_outliers", "k_row_scan",
+    "k_quant_lorenzo_split_hist", "k_codebook", "k_lengths", "k_scan",
+    "k_pack", "k_clear", "k_decode_tables", "k_decode", "k_patch_outliers", "k_row_scan",
     "k_col_scan_dequant", "k_decode_fused", "k_decode_fused_rest", "k_controller_stats"};
 }  // namespace cmpz
 
 using namespace cmpz;
 
+// Device memory of a context, carved out of one block (from hipMalloc in cmp_create).
+struct Scratch {
+    // compression (see BatchC)
+    uint16_t   *sym;
+    uint32_t   *hist, *hist_copy, *enc32, *outl_cnt, *chunk_bits, *range_units, *range_outl, *range_bits, *status;
+    uint8_t    *lens;
+    uint64_t   *codes;
+    TensorMeta *tmeta;
+    // decompression
+    uint32_t   *meta;
+    void       *tables;
+    uint32_t   *items;          // item list of the fused decode kernels
+    ControllerScratch *ctl;
+    ControllerResult  *ctl_result;
+    uint64_t    max_chunks;     // chunks the symbol scratch holds
+    uint64_t    max_ranges;
+};
+
 struct cmp_ctx {
     cmp_config cfg;
     int        device;
-    uint64_t   max_chunks;
-    uint8_t   *d_base;          // one allocation, carved up below
-    uint16_t  *d_sym;
-    uint32_t  *d_hist, *d_hist_copy, *d_meta, *d_status, *d_outl_cnt;
-    uint64_t  *d_desc;
-    uint8_t   *d_lens;
-    uint64_t  *d_codes;
-    void      *d_tables;
-    uint32_t  *d_items;      // item list of the fused decode kernels
-    uint32_t  *h_hint;       // pinned host word the decode kernels report to (see launch_decode_fused)
-    uint32_t  *d_hint;       // its device address
-    ControllerScratch *d_ctl;
-    ControllerResult  *d_ctl_result;
-    uint64_t   last_numel;
-    CompressArgs pending;       // what cmp_compress_begin left for cmp_compress_finish
+    uint8_t   *d_base;          // one allocation, carved up into `s`
+    Scratch    s;
+    uint32_t  *h_hint;          // pinned host word the decode kernels report to (see launch_decode_fused)
+    uint32_t  *d_hint;          // its device address
+    uint64_t   last_numel;      // first tensor of the latest compress call (cmp_debug_stage)
+    const uint8_t *last_out;
+    BatchC     pending;         // what cmp_compress_begin left for cmp_compress_finish
     bool       has_pending;
     Profiler   prof;
 };
@@ -49,7 +59,7 @@ bool config_ok(const cmp_config &c)
     if (c.chunk != kChunk) return false;
     if (c.sub != 32 && c.sub != 64 && c.sub != 128) return false;
     if (c.guard_shift < 1 || c.guard_shift > 23) return false;
-    if (c.max_numel >= (1ull << 32)) return false;
+    if (c.max_numel > kMaxNumel) return false;
     return true;
 }
 
@@ -60,7 +70,7 @@ bool shape_numel(const int64_t shape[4], uint64_t *numel)
     for (int i = 0; i < 4; ++i) {
         if (shape[i] < 0 || shape[i] > 0xffffffffLL) return false;
         n *= (uint64_t)shape[i];
-        if (n >= (1ull << 32)) return false;
+        if (n > kMaxNumel) return false;
     }
     *numel = n;
     return true;
@@ -79,17 +89,39 @@ bool constants(float eb, uint32_t guard_shift, float *s, float *r)
     return true;
 }
 
-Layout make_layout(uint64_t numel, const cmp_config &c)
+Layout make_layout(uint64_t numel, const cmp_config &c) { return cmpz::make_layout(numel, c.radius, c.sub); }
+
+// Carves the scratch of a context for `max_numel` elements per call out of a block starting at
+// `base` (NULL: only the size is wanted).  Returns the bytes needed; *zero_from is the offset
+// from which the block must start out as zeros (everything but the symbols).
+uint64_t carve_scratch(Scratch *sc, uint8_t *base, uint64_t max_numel, uint64_t *zero_from)
 {
-    Layout l;
-    l.nchunks = (uint32_t)((numel + c.chunk - 1) / c.chunk);
-    l.nsub = c.chunk / c.sub;
-    l.off_lens = kHeaderBytes;
-    l.off_chunk_off = l.off_lens + align_up(2ull * c.radius, 16);
-    l.off_outl_off = l.off_chunk_off + align_up(4ull * ((uint64_t)l.nchunks + 1), 16);
-    l.off_sub_bits = l.off_outl_off + align_up(4ull * ((uint64_t)l.nchunks + 1), 16);
-    l.off_payload = l.off_sub_bits + align_up(2ull * (uint64_t)l.nchunks * l.nsub, 16);
-    return l;
+    Scratch s;
+    s.max_chunks = (max_numel + kChunk - 1) / kChunk + kBatchMax;       // every tensor of a call rounds up
+    s.max_ranges = (s.max_chunks + kPackChunks - 1) / kPackChunks + kBatchMax;
+    uint64_t off = 0;
+    auto carve = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, 256); return base + o; };
+    s.sym = reinterpret_cast<uint16_t *>(carve(2 * (s.max_chunks * kChunk + 16)));   // whole chunks: readable past numel
+    if (zero_from) *zero_from = off;
+    s.hist = reinterpret_cast<uint32_t *>(carve(4ull * kMaxSym * kHistCopies * kBatchMax));
+    s.hist_copy = reinterpret_cast<uint32_t *>(carve(4ull * kMaxSym * kBatchMax));
+    s.lens = carve(1ull * kMaxSym * kBatchMax);
+    s.codes = reinterpret_cast<uint64_t *>(carve(8ull * kMaxSym * kBatchMax));
+    s.enc32 = reinterpret_cast<uint32_t *>(carve(4ull * kMaxSym * kBatchMax));
+    s.outl_cnt = reinterpret_cast<uint32_t *>(carve(4 * s.max_chunks));
+    s.chunk_bits = reinterpret_cast<uint32_t *>(carve(4 * s.max_chunks));
+    s.range_units = reinterpret_cast<uint32_t *>(carve(4 * s.max_ranges));
+    s.range_outl = reinterpret_cast<uint32_t *>(carve(4 * s.max_ranges));
+    s.range_bits = reinterpret_cast<uint32_t *>(carve(4 * s.max_ranges));
+    s.tmeta = reinterpret_cast<TensorMeta *>(carve(sizeof(TensorMeta) * kBatchMax));
+    s.status = reinterpret_cast<uint32_t *>(carve(4));
+    s.meta = reinterpret_cast<uint32_t *>(carve(4 * kMetaWords));
+    s.tables = carve(decode_tables_bytes());
+    s.items = reinterpret_cast<uint32_t *>(carve(4 * fused_item_words(max_numel)));
+    s.ctl = reinterpret_cast<ControllerScratch *>(carve(sizeof(ControllerScratch)));
+    s.ctl_result = reinterpret_cast<ControllerResult *>(carve(sizeof(ControllerResult)));
+    if (sc) *sc = s;
+    return off;
 }
 
 struct DeviceGuard {
@@ -142,41 +174,18 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
     if (!ctx) return CMP_E_HIP;
     ctx->cfg = c;
     ctx->device = device;
-    ctx->max_chunks = (c.max_numel + c.chunk - 1) / c.chunk;
     ctx->last_numel = 0;
+    ctx->last_out = nullptr;
     ctx->has_pending = false;
 
-    uint64_t off = 0;
-    auto carve = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, 256); return o; };
-    const uint64_t o_sym = carve(2 * (ctx->max_chunks * c.chunk + 16));   // whole chunks: readable past numel
-    const uint64_t o_hist = carve(4 * kMaxSym * kHistCopies);
-    const uint64_t o_hist_copy = carve(4 * kMaxSym);
-    const uint64_t o_desc = carve(8 * (ctx->max_chunks + 1));
-    const uint64_t o_ocnt = carve(4 * (ctx->max_chunks + 1));
-    const uint64_t o_meta = carve(4 * kMetaWords);
-    const uint64_t o_status = carve(4);
-    const uint64_t o_lens = carve(kMaxSym);
-    const uint64_t o_codes = carve(8 * kMaxSym);
-    const uint64_t o_tables = carve(decode_tables_bytes());
-    const uint64_t o_items = carve(4 * fused_item_words(c.max_numel));
-    const uint64_t o_ctl = carve(sizeof(ControllerScratch));
-    const uint64_t o_ctl_result = carve(sizeof(ControllerResult));
-    if (hipMalloc(reinterpret_cast<void **>(&ctx->d_base), off) != hipSuccess) { delete ctx; return CMP_E_HIP; }
+    uint64_t zero_from = 0;
+    const uint64_t bytes = carve_scratch(nullptr, nullptr, c.max_numel, &zero_from);
+    if (hipMalloc(reinterpret_cast<void **>(&ctx->d_base), bytes) != hipSuccess) { delete ctx; return CMP_E_HIP; }
     // only the small control words need a defined start value; the symbol scratch does not
-    if (hipMemset(ctx->d_base + o_hist, 0, off - o_hist) != hipSuccess) {
+    if (hipMemset(ctx->d_base + zero_from, 0, bytes - zero_from) != hipSuccess) {
         (void)hipFree(ctx->d_base); delete ctx; return CMP_E_HIP;
     }
-    ctx->d_sym = reinterpret_cast<uint16_t *>(ctx->d_base + o_sym);
-    ctx->d_hist = reinterpret_cast<uint32_t *>(ctx->d_base + o_hist);
-    ctx->d_hist_copy = reinterpret_cast<uint32_t *>(ctx->d_base + o_hist_copy);
-    ctx->d_desc = reinterpret_cast<uint64_t *>(ctx->d_base + o_desc);
-    ctx->d_outl_cnt = reinterpret_cast<uint32_t *>(ctx->d_base + o_ocnt);
-    ctx->d_meta = reinterpret_cast<uint32_t *>(ctx->d_base + o_meta);
-    ctx->d_status = reinterpret_cast<uint32_t *>(ctx->d_base + o_status);
-    ctx->d_lens = ctx->d_base + o_lens;
-    ctx->d_codes = reinterpret_cast<uint64_t *>(ctx->d_base + o_codes);
-    ctx->d_tables = ctx->d_base + o_tables;
-    ctx->d_items = reinterpret_cast<uint32_t *>(ctx->d_base + o_items);
+    carve_scratch(&ctx->s, ctx->d_base, c.max_numel, nullptr);
     ctx->h_hint = nullptr; ctx->d_hint = nullptr;
     if (hipHostMalloc(reinterpret_cast<void **>(&ctx->h_hint), 64, hipHostMallocMapped) != hipSuccess ||
         hipHostGetDevicePointer(reinterpret_cast<void **>(&ctx->d_hint), ctx->h_hint, 0) != hipSuccess) {
@@ -184,8 +193,6 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
         (void)hipFree(ctx->d_base); delete ctx; return CMP_E_HIP;
     }
     *ctx->h_hint = 1;                                  // nothing known yet: assume listed items
-    ctx->d_ctl = reinterpret_cast<ControllerScratch *>(ctx->d_base + o_ctl);
-    ctx->d_ctl_result = reinterpret_cast<ControllerResult *>(ctx->d_base + o_ctl_result);
     *out = ctx;
     return CMP_OK;
 }
@@ -216,77 +223,165 @@ size_t cmp_bound(const cmp_ctx *ctx, const int64_t shape[4])
 
 namespace {
 
-// Argument checks and everything of CompressArgs that does not depend on the output buffer.
-int fill_compress_args(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, CompressArgs *out)
+// One tensor of a compress call after the argument checks.
+struct CheckedTensor {
+    const float *x;
+    uint32_t shape[4];
+    uint64_t numel;
+    uint32_t eb_bits;
+    float r;
+    Layout lay;
+};
+
+int check_tensor(const cmp_config &cfg, const float *d_x, const int64_t shape[4], float eb, CheckedTensor *out)
 {
     uint64_t numel;
     float s, r;
-    if (!ctx || !shape_numel(shape, &numel)) return CMP_E_ARG;
-    if (numel > ctx->cfg.max_numel || (numel > 0 && !d_x)) return CMP_E_ARG;
-    if (!constants(eb, ctx->cfg.guard_shift, &s, &r)) return CMP_E_ARG;
+    if (!shape_numel(shape, &numel)) return CMP_E_ARG;
+    if (numel > cfg.max_numel || (numel > 0 && !d_x)) return CMP_E_ARG;
+    if (!constants(eb, cfg.guard_shift, &s, &r)) return CMP_E_ARG;
     if (reinterpret_cast<uintptr_t>(d_x) & 15) return CMP_E_ARG;
-
-    CompressArgs a;
-    std::memset(&a, 0, sizeof(a));
-    a.lay = make_layout(numel, ctx->cfg);
-    a.x = d_x;
-    a.numel = (uint32_t)numel;
-    a.H = (uint32_t)shape[2]; a.W = (uint32_t)shape[3]; a.HW = a.H * a.W;
-    for (int i = 0; i < 4; ++i) a.shape[i] = (uint32_t)shape[i];
-    a.radius = ctx->cfg.radius; a.sub = ctx->cfg.sub; a.guard_shift = ctx->cfg.guard_shift;
-    std::memcpy(&a.eb_bits, &eb, 4);
-    a.r = r;
-    a.sym = ctx->d_sym; a.hist = ctx->d_hist; a.hist_copy = ctx->d_hist_copy;
-    a.lens = ctx->d_lens; a.codes = ctx->d_codes;
-    a.desc = ctx->d_desc; a.outl_cnt = ctx->d_outl_cnt;
-    // encode tiles: every tile costs one ticket (a serialised atomic), so as large as still
-    // leaves several hundred of them to spread over the chip
-    a.tile_chunks = 8;
-    while (a.tile_chunks > 1 && (a.lay.nchunks + a.tile_chunks - 1) / a.tile_chunks < 768) a.tile_chunks >>= 1;
-    a.meta = ctx->d_meta; a.status = ctx->d_status;
-    *out = a;
+    out->x = d_x;
+    for (int i = 0; i < 4; ++i) out->shape[i] = (uint32_t)shape[i];
+    out->numel = numel;
+    std::memcpy(&out->eb_bits, &eb, 4);
+    out->r = r;
+    out->lay = make_layout(numel, cfg);
     return CMP_OK;
+}
+
+// The launch group's common part: configuration and scratch pointers.
+void group_begin(BatchC *b, const cmp_config &cfg, const Scratch &s)
+{
+    std::memset(b, 0, sizeof(*b));
+    b->radius = cfg.radius; b->sub = cfg.sub; b->guard_shift = cfg.guard_shift;
+    b->sym = s.sym; b->hist = s.hist; b->hist_copy = s.hist_copy; b->lens = s.lens; b->codes = s.codes;
+    b->enc32 = s.enc32; b->outl_cnt = s.outl_cnt; b->chunk_bits = s.chunk_bits;
+    b->range_units = s.range_units; b->range_outl = s.range_outl; b->range_bits = s.range_bits;
+    b->tmeta = s.tmeta; b->status = s.status;
+}
+
+void group_add(BatchC *b, const CheckedTensor &c, void *d_out, size_t out_cap)
+{
+    TensorC &t = b->t[b->n++];
+    t.x = c.x; t.out = static_cast<uint8_t *>(d_out); t.out_cap = out_cap;
+    for (int i = 0; i < 4; ++i) t.shape[i] = c.shape[i];
+    t.numel = (uint32_t)c.numel; t.nchunks = c.lay.nchunks; t.eb_bits = c.eb_bits; t.r = c.r;
+    t.chunk_base = b->total_chunks;
+    t.pack_base = b->pack_wgs;
+    b->total_chunks += t.nchunks;
+    b->pack_wgs += (t.nchunks + kPackChunks - 1) / kPackChunks;
+    t.divW = FastDiv::make(c.shape[3]);
+    t.divHW = FastDiv::make(c.shape[2] * c.shape[3]);
+}
+
+// Workgroups of the first sweep: few, long-lived ones (every workgroup ends with a flush of its
+// histogram, contended atomics), but still several per CU.  Tensors whose rows do not fit the
+// tiled kernel get none here and a launch of the untiled kernel each.
+void group_plan_sweep(BatchC *b)
+{
+    b->sweep_chunks = (b->total_chunks + 2047) / 2048;
+    if (b->sweep_chunks < 1) b->sweep_chunks = 1;
+    b->sweep_wgs = 0;
+    for (uint32_t k = 0; k < b->n; ++k) {
+        TensorC &t = b->t[k];
+        t.sweep_base = b->sweep_wgs;
+        if (sweep1_tiled_fits(t.shape[3])) b->sweep_wgs += (t.nchunks + b->sweep_chunks - 1) / b->sweep_chunks;
+    }
+}
+
+void group_launch_begin(const BatchC &b, Profiler *prof, hipStream_t st)
+{
+    launch_sweep1(b, prof, st);
+    for (uint32_t k = 0; k < b.n; ++k)
+        if (!sweep1_tiled_fits(b.t[k].shape[3])) launch_sweep1_untiled(b, k, prof, st);
+}
+
+void group_launch_finish(const BatchC &b, Profiler *prof, hipStream_t st)
+{
+    launch_codebook(b, prof, st);
+    launch_pack(b, prof, st);
 }
 
 }  // namespace
 
-int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *d_out,
-                 size_t out_cap, size_t *h_size, void *stream)
+int cmp_compress_batch(cmp_ctx *ctx, int n, const float *const *d_x, const int64_t (*shapes)[4], const float *eb,
+                       void *const *d_out, const size_t *out_cap, size_t *h_sizes, void *stream)
 {
-    CompressArgs a;
-    if (!d_out || (reinterpret_cast<uintptr_t>(d_out) & 15)) return CMP_E_ARG;
-    const int rc = fill_compress_args(ctx, d_x, shape, eb, &a);
-    if (rc != CMP_OK) return rc;
+    if (!ctx || n < 0 || (n > 0 && (!d_x || !shapes || !eb || !d_out || !out_cap))) return CMP_E_ARG;
     if (ctx->has_pending) return CMP_E_ARG;                  // between cmp_compress_begin and _finish
-    if (out_cap < a.lay.off_payload) {
-        if (h_size) *h_size = (size_t)a.lay.off_payload;
-        return CMP_E_NOSPACE;
+    // every argument is checked before anything is launched
+    std::vector<CheckedTensor> ck((size_t)n);
+    int rc_space = CMP_OK;
+    for (int i = 0; i < n; ++i) {
+        const int rc = check_tensor(ctx->cfg, d_x[i], shapes[i], eb[i], &ck[i]);
+        if (rc != CMP_OK) return rc;
+        if (!d_out[i] || (reinterpret_cast<uintptr_t>(d_out[i]) & 15)) return CMP_E_ARG;
+        if (out_cap[i] < ck[i].lay.off_payload) {
+            if (h_sizes) h_sizes[i] = (size_t)ck[i].lay.off_payload;
+            rc_space = CMP_E_NOSPACE;
+        }
     }
-    a.out = static_cast<uint8_t *>(d_out);
-    a.out_cap = out_cap;
+    if (rc_space != CMP_OK) return rc_space;
 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    launch_compress_begin(a, &ctx->prof, st);
-    launch_compress_finish(a, &ctx->prof, st);
-    ctx->last_numel = a.numel;
+    // launch groups: at most kBatchMax tensors and max_numel elements each; the groups of a call
+    // use the same scratch one after the other, in stream order
+    int i = 0;
+    while (i < n) {
+        BatchC b;
+        group_begin(&b, ctx->cfg, ctx->s);
+        uint64_t elems = 0;
+        while (i < n && b.n < (uint32_t)kBatchMax && (b.n == 0 || elems + ck[i].numel <= ctx->cfg.max_numel)) {
+            elems += ck[i].numel;
+            group_add(&b, ck[i], d_out[i], out_cap[i]);
+            ++i;
+        }
+        group_plan_sweep(&b);
+        group_launch_begin(b, &ctx->prof, st);
+        group_launch_finish(b, &ctx->prof, st);
+        ctx->last_numel = b.t[0].numel;
+        ctx->last_out = b.t[0].out;
+    }
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
-    if (h_size) return cmp_compressed_size(ctx, d_out, h_size, stream);
-    return CMP_OK;
+    int worst = CMP_OK;
+    if (h_sizes) {
+        for (int k = 0; k < n; ++k) {
+            const int rc = cmp_compressed_size(ctx, d_out[k], &h_sizes[k], stream);
+            if (rc < 0 && (worst >= 0 || rc < worst)) worst = rc;
+            else if (rc > 0 && worst == CMP_OK) worst = rc;
+        }
+    }
+    return worst;
+}
+
+int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *d_out,
+                 size_t out_cap, size_t *h_size, void *stream)
+{
+    if (!shape) return CMP_E_ARG;
+    const float *xs[1] = {d_x};
+    void *outs[1] = {d_out};
+    return cmp_compress_batch(ctx, 1, xs, reinterpret_cast<const int64_t (*)[4]>(shape), &eb, outs, &out_cap, h_size,
+                              stream);
 }
 
 int cmp_compress_begin(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *stream)
 {
-    CompressArgs a;
-    const int rc = fill_compress_args(ctx, d_x, shape, eb, &a);
+    if (!ctx) return CMP_E_ARG;
+    CheckedTensor c;
+    const int rc = check_tensor(ctx->cfg, d_x, shape, eb, &c);
     if (rc != CMP_OK) return rc;
     if (ctx->has_pending) return CMP_E_ARG;                  // the previous begin was never finished
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
-    launch_compress_begin(a, &ctx->prof, static_cast<hipStream_t>(stream));
+    BatchC &b = ctx->pending;
+    group_begin(&b, ctx->cfg, ctx->s);
+    group_add(&b, c, nullptr, 0);
+    group_plan_sweep(&b);
+    group_launch_begin(b, &ctx->prof, static_cast<hipStream_t>(stream));
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
-    ctx->pending = a;
     ctx->has_pending = true;
     return CMP_OK;
 }
@@ -295,22 +390,24 @@ int cmp_compress_finish(cmp_ctx *ctx, void *d_out, size_t out_cap, size_t *h_siz
 {
     if (!ctx || !ctx->has_pending) return CMP_E_ARG;
     if (!d_out || (reinterpret_cast<uintptr_t>(d_out) & 15)) return CMP_E_ARG;
-    CompressArgs a = ctx->pending;
+    BatchC &b = ctx->pending;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
     ctx->has_pending = false;
-    if (out_cap < a.lay.off_payload) {
+    const uint64_t fixed = make_layout(b.t[0].numel, ctx->cfg).off_payload;
+    if (out_cap < fixed) {
         // nothing can be written; drop what the first sweep accumulated so that the context is clean
-        if (hipMemsetAsync(ctx->d_hist, 0, 4 * kMaxSym * kHistCopies, st) != hipSuccess) return CMP_E_HIP;
-        if (hipMemsetAsync(ctx->d_meta + kMetaRangeEvents, 0, 4, st) != hipSuccess) return CMP_E_HIP;
-        if (h_size) *h_size = (size_t)a.lay.off_payload;
+        launch_clear(b, &ctx->prof, st);
+        if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
+        if (h_size) *h_size = (size_t)fixed;
         return CMP_E_NOSPACE;
     }
-    a.out = static_cast<uint8_t *>(d_out);
-    a.out_cap = out_cap;
-    launch_compress_finish(a, &ctx->prof, st);
-    ctx->last_numel = a.numel;
+    b.t[0].out = static_cast<uint8_t *>(d_out);
+    b.t[0].out_cap = out_cap;
+    group_launch_finish(b, &ctx->prof, st);
+    ctx->last_numel = b.t[0].numel;
+    ctx->last_out = b.t[0].out;
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
     if (h_size) return cmp_compressed_size(ctx, d_out, h_size, stream);
     return CMP_OK;
@@ -356,11 +453,11 @@ int cmp_decompress(cmp_ctx *ctx, const void *d_buf, size_t size, const int64_t s
     a.radius = ctx->cfg.radius; a.sub = ctx->cfg.sub; a.guard_shift = ctx->cfg.guard_shift;
     std::memcpy(&a.eb_bits, &eb, 4);
     a.s = s;
-    a.meta = ctx->d_meta; a.status = ctx->d_status;
+    a.meta = ctx->s.meta; a.status = ctx->s.status;
 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
-    launch_decompress(a, ctx->d_tables, ctx->d_items, ctx->h_hint, ctx->d_hint, &ctx->prof,
+    launch_decompress(a, ctx->s.tables, ctx->s.items, ctx->h_hint, ctx->d_hint, &ctx->prof,
                       static_cast<hipStream_t>(stream));
     if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
     return CMP_OK;
@@ -373,11 +470,11 @@ int cmp_last_status(cmp_ctx *ctx, void *stream)
     if (!guard.ok) return CMP_E_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint32_t word = 0;
-    if (hipMemcpyAsync(&word, ctx->d_status, 4, hipMemcpyDeviceToHost, st) != hipSuccess) return CMP_E_HIP;
+    if (hipMemcpyAsync(&word, ctx->s.status, 4, hipMemcpyDeviceToHost, st) != hipSuccess) return CMP_E_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return CMP_E_HIP;
     if (word) {
         const uint32_t zero = 0;
-        if (hipMemcpyAsync(ctx->d_status, &zero, 4, hipMemcpyHostToDevice, st) != hipSuccess) return CMP_E_HIP;
+        if (hipMemcpyAsync(ctx->s.status, &zero, 4, hipMemcpyHostToDevice, st) != hipSuccess) return CMP_E_HIP;
         if (hipStreamSynchronize(st) != hipSuccess) return CMP_E_HIP;
     }
     return status_to_code(word);
@@ -388,11 +485,24 @@ int cmp_debug_stage(cmp_ctx *ctx, int which, const void **d_ptr, size_t *bytes)
     if (!ctx || !d_ptr || !bytes) return CMP_E_ARG;
     const size_t nsym = 2 * (size_t)ctx->cfg.radius;
     switch (which) {
-    case CMP_STAGE_QUANT_CODES: *d_ptr = ctx->d_sym; *bytes = 2 * (size_t)ctx->last_numel; return CMP_OK;
-    case CMP_STAGE_HIST: *d_ptr = ctx->d_hist_copy; *bytes = 4 * nsym; return CMP_OK;
-    case CMP_STAGE_LENS: *d_ptr = ctx->d_lens; *bytes = nsym; return CMP_OK;
-    case CMP_STAGE_CODES: *d_ptr = ctx->d_codes; *bytes = 8 * nsym; return CMP_OK;
-    case CMP_STAGE_COUNTERS: *d_ptr = ctx->d_meta; *bytes = 4 * kMetaWords; return CMP_OK;
+    case CMP_STAGE_QUANT_CODES: *d_ptr = ctx->s.sym; *bytes = 2 * (size_t)ctx->last_numel; return CMP_OK;
+    case CMP_STAGE_HIST: *d_ptr = ctx->s.hist_copy; *bytes = 4 * nsym; return CMP_OK;
+    case CMP_STAGE_LENS: *d_ptr = ctx->s.lens; *bytes = nsym; return CMP_OK;
+    case CMP_STAGE_CODES: *d_ptr = ctx->s.codes; *bytes = 8 * nsym; return CMP_OK;
+    case CMP_STAGE_OUTLIER_IDX:
+    case CMP_STAGE_OUTLIER_VAL: {
+        // the records live in the container: its header says where
+        if (!ctx->last_out) return CMP_E_ARG;
+        DeviceGuard guard(ctx->device);
+        if (!guard.ok) return CMP_E_HIP;
+        Header hd;
+        if (hipDeviceSynchronize() != hipSuccess) return CMP_E_HIP;
+        if (hipMemcpy(&hd, ctx->last_out, sizeof(hd), hipMemcpyDeviceToHost) != hipSuccess) return CMP_E_HIP;
+        if (hd.magic != kMagic || hd.status != 0) return CMP_E_FORMAT;
+        *d_ptr = ctx->last_out + (which == CMP_STAGE_OUTLIER_IDX ? hd.off_outl_idx : hd.off_outl_val);
+        *bytes = 4 * (size_t)hd.n_outliers;
+        return CMP_OK;
+    }
     default: return CMP_E_ARG;
     }
 }
@@ -444,8 +554,8 @@ int cmp_estimate_eb(cmp_ctx *ctx, const float *d_act, uint64_t act_numel, const 
     if (cfg) c = *cfg; else cmp_default_controller_config(&c);
     if (!(c.eb_min > 0.0f) || !(c.eb_max >= c.eb_min) || !(c.sigma_frac > 0.0f) || !(c.a > 0.0f)) return CMP_E_ARG;
     if (act_numel == 0 || batch_n == 0 || per_sample == 0 || mom_numel == 0) return CMP_E_ARG;
-    if (batch_n > kMaxBatch || per_sample >= (1ull << 32) || batch_n * per_sample >= (1ull << 32)) return CMP_E_ARG;
-    if (act_numel >= (1ull << 32) || mom_numel >= (1ull << 32)) return CMP_E_ARG;
+    if (batch_n > kMaxBatch || per_sample > kMaxNumel || batch_n * per_sample > kMaxNumel) return CMP_E_ARG;
+    if (act_numel > kMaxNumel || mom_numel > kMaxNumel) return CMP_E_ARG;
     if ((reinterpret_cast<uintptr_t>(d_act) | reinterpret_cast<uintptr_t>(d_loss) | reinterpret_cast<uintptr_t>(d_mom)) & 15)
         return CMP_E_ARG;
 
@@ -454,14 +564,14 @@ int cmp_estimate_eb(cmp_ctx *ctx, const float *d_act, uint64_t act_numel, const 
     a.n_act = (uint32_t)act_numel; a.n_loss = (uint32_t)(batch_n * per_sample); a.n_mom = (uint32_t)mom_numel;
     a.batch_n = (uint32_t)batch_n; a.per_sample = (uint32_t)per_sample;
     a.sigma_frac = c.sigma_frac; a.a = c.a; a.eb_min = c.eb_min; a.eb_max = c.eb_max;
-    a.scratch = ctx->d_ctl; a.result = ctx->d_ctl_result;
+    a.scratch = ctx->s.ctl; a.result = ctx->s.ctl_result;
 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return CMP_E_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
     launch_controller(a, &ctx->prof, st);
     ControllerResult res;
-    if (hipMemcpyAsync(&res, ctx->d_ctl_result, sizeof(res), hipMemcpyDeviceToHost, st) != hipSuccess) return CMP_E_HIP;
+    if (hipMemcpyAsync(&res, ctx->s.ctl_result, sizeof(res), hipMemcpyDeviceToHost, st) != hipSuccess) return CMP_E_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return CMP_E_HIP;
     *h_eb = res.eb;
     if (h_stats) { h_stats[0] = res.stats[0]; h_stats[1] = res.stats[1]; h_stats[2] = res.stats[2]; }

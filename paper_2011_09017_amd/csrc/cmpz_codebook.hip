@@ -18,23 +18,17 @@ namespace {
 constexpr int kCbThreads = 1024;
 constexpr uint32_t kInf = 0xffffffffu;       // "queue empty"; a real weight reaches it only at the root
 
-#ifdef CMPZ_PHASE_CLOCKS
-#define PHASE(k) if (tid == 0) { const long long now_ = clock64(); clk[k] += now_ - last_; last_ = now_; }
-#else
-#define PHASE(k)
-#endif
-
 __device__ __forceinline__ uint32_t rdlane(uint32_t v, uint32_t l)
 {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)l);
 }
 
-__global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
+__global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
 {
-#ifdef CMPZ_PHASE_CLOCKS
-    long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    long long last_ = clock64();
-#endif
+    // one workgroup per tensor of the group
+    const uint32_t ti = blockIdx.x;
+    uint32_t *__restrict__ g_hist = b.hist + (uint64_t)ti * kHistCopies * kMaxSym;
+    uint8_t *__restrict__ out = b.t[ti].out;
     __shared__ uint64_t key[kMaxSym];            // used symbols, compacted: count << 10 | symbol
     __shared__ uint32_t leaf_w[kMaxSym + 192];   // leaf weights, ascending, padded with kInf
     __shared__ uint16_t leaf_sym[kMaxSym];
@@ -49,21 +43,20 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
     __shared__ uint32_t max_len_s;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const uint32_t nsym = 2 * a.radius;
+    const uint32_t nsym = 2 * b.radius;
 
     // 1. fetch the histogram, leave it zeroed for the next call, keep a copy for inspection
     uint32_t cnt = 0;
 #pragma unroll
     for (uint32_t k = 0; k < kHistCopies; ++k) {
-        if ((uint32_t)tid < nsym) cnt += a.hist[k * kMaxSym + tid];
-        a.hist[k * kMaxSym + tid] = 0;
+        if ((uint32_t)tid < nsym) cnt += g_hist[k * kMaxSym + tid];
+        g_hist[k * kMaxSym + tid] = 0;
     }
-    a.hist_copy[tid] = cnt;
+    b.hist_copy[ti * kMaxSym + tid] = cnt;
     len_of[tid] = 0;
     if (tid < 64) { bl_count[tid] = 0; first_code[tid] = 0; }
     if (tid == 0) max_len_s = 0;
 
-    PHASE(0)
     // 2. compact the used symbols (ballot + per-wave offsets)
     const unsigned long long used_mask = __ballot(cnt != 0);
     if (lane == 0) wave_used[wv] = (uint32_t)__popcll(used_mask);
@@ -74,7 +67,6 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
     if (cnt) key[my_slot] = ((uint64_t)cnt << 10) | (uint64_t)tid;
     __syncthreads();
 
-    PHASE(1)
     // 3. sort by counting: the rank of a key is the number of smaller keys (keys are distinct)
     if ((uint32_t)tid < n) {
         const uint64_t mine = key[tid];
@@ -89,7 +81,6 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
     if (tid < 192) node_w[kMaxSym + tid] = kInf;
     __syncthreads();
 
-    PHASE(2)
     // 4. two-queue merge by wave 0.  Lane j of LB holds the weight of leaf lbase+j, lane j of IB
     //    that of internal node ibase+j (kInf = not made yet).  The two lightest unused nodes of
     //    either queue are kept in scalar registers; step m makes internal node m and logs its
@@ -210,7 +201,6 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
     }
     __syncthreads();
 
-    PHASE(3)
     // 5. depth of every leaf = its code length
     if ((uint32_t)tid < n) {
         uint32_t depth = 0;
@@ -225,7 +215,6 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
     }
     __syncthreads();
 
-    PHASE(4)
     // 6. canonical codes: first code of each length, then rank within the length
     if (tid == 0) {
         uint64_t code = 0;
@@ -237,25 +226,22 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(CompressArgs a)
     const uint32_t L = len_of[tid];
     const uint32_t rank = rank_within_length(L, wave_cnt, tid);       // contains barriers
     const uint64_t entry = L ? (((uint64_t)L << 56) | (first_code[L] + rank)) : 0ull;
-    a.codes[tid] = entry;
-    a.lens[tid] = (uint8_t)L;
+    b.codes[ti * kMaxSym + tid] = entry;
+    b.lens[ti * kMaxSym + tid] = (uint8_t)L;
+    // what the packing kernel looks up while no codeword is longer than 27 bits: the codeword
+    // left-aligned in 32 bits with its length in the low five
+    b.enc32[ti * kMaxSym + tid] = (L && L <= 27u) ? (((uint32_t)entry << (32u - L)) | L) : 0u;
     // container section `lens`: 2*radius bytes, zero padded to a multiple of 16
     const uint32_t padded = (nsym + 15u) & ~15u;
-    if ((uint32_t)tid < padded) a.out[a.lay.off_lens + tid] = ((uint32_t)tid < nsym) ? (uint8_t)L : 0;
-    if (tid == 0) a.meta[kMetaMaxLen] = max_len_s;
-    PHASE(5)
-#ifdef CMPZ_PHASE_CLOCKS
-    if (tid == 0)
-        for (int k = 0; k < 8; ++k)
-            atomicAdd(reinterpret_cast<unsigned long long *>(a.meta + kMetaClocks) + 16 + k, (unsigned long long)clk[k]);
-#endif
+    if ((uint32_t)tid < padded) out[kHeaderBytes + tid] = ((uint32_t)tid < nsym) ? (uint8_t)L : 0;
+    if (tid == 0) b.tmeta[ti].max_len = max_len_s;
 }
 
 }  // namespace
 
-void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st)
+void launch_codebook(const BatchC &b, Profiler *prof, hipStream_t st)
 {
-    launch(prof, kKCodebook, k_codebook, dim3(1), dim3(kCbThreads), st, a);
+    launch(prof, kKCodebook, k_codebook, dim3(b.n), dim3(kCbThreads), st, b);
 }
 
 }  // namespace cmpz

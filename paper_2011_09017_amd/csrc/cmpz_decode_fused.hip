@@ -325,7 +325,8 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
             const uint32_t uu0 = fa.uu0, uu1 = fa.uu1;
             bool lbad = !(uu0 <= uu1 && uu1 <= payload_units);
             const uint32_t nw = lbad ? 0u : (uu1 - uu0) * 4;
-            if ((uint64_t)start + sbits > (uint64_t)nw * 32) lbad = true;
+            // a sub-block holds at least one codeword of at least one bit: an empty chunk stream is damage
+            if (nw == 0 || (uint64_t)start + sbits > (uint64_t)nw * 32) lbad = true;
             const uint32_t el0 = g << kLog;              // first element of the sub-block
             const uint32_t n_here = (a.numel - el0 >= (uint32_t)SUB) ? (uint32_t)SUB : a.numel - el0;
             // elements of this sub-block that belong to the band: k in [klo, khi)

@@ -14,6 +14,9 @@ constexpr uint32_t kChunk       = 4096;     // codes per Huffman chunk (fixed on
 constexpr uint32_t kMaxSym      = 1024;     // 2 * largest radius
 constexpr int      kQMax        = 16384;    // clamp of the pre-quantised integer
 constexpr uint32_t kHeaderBytes = 256;
+// Largest array the kernels index with 32 bits: their loop counters step by up to 4096 past the
+// last element before they compare, so the bound stays two such steps below 2^32.
+constexpr uint64_t kMaxNumel    = (1ull << 32) - 8192;
 constexpr uint32_t kMaxCodeLen  = 48;       // counts below 2^32 bound a Huffman depth by 45
 constexpr uint32_t kVersion     = 1;
 constexpr uint32_t kHistCopies  = 8;        // global histogram replicas that workgroups flush into (less contention)
@@ -50,65 +53,6 @@ constexpr uint32_t kStFormat   = 4u;
 constexpr uint32_t kStMismatch = 8u;
 constexpr uint32_t kStInternal = 16u;       // a bounded wait ran out (reported as CMP_E_HIP)
 
-// Tile descriptors of the encode sweep's single-pass scan: bits 63..62 state,
-// bits 61..32 payload units, bits 31..0 outlier count.  The first sweep leaves 0.
-constexpr uint64_t kDescAgg    = 1ull << 62;   // value = this tile alone
-constexpr uint64_t kDescPrefix = 2ull << 62;   // value = all tiles up to and including this one
-constexpr uint64_t kDescMask   = (1ull << 62) - 1;
-
-// Scratch words in ctx->d_meta.
-enum MetaWord : int {
-    kMetaRangeEvents = 0,   // elements clamped by the current compress
-    kMetaMaxLen      = 1,   // longest codeword of the current codebook
-    kMetaSkip        = 2,   // nonzero: container does not fit, later kernels write nothing
-    kMetaNOutliers   = 3,
-    kMetaBad         = 4,   // decompress: nonzero when the container failed validation
-    kMetaTicket      = 5,   // next chunk to hand out in the encode sweep (zero between calls)
-    kMetaDone        = 6,   // workgroups of the encode sweep that have finished (zero between calls)
-    kMetaTotalUnits  = 7,   // payload size in 16-byte units
-    kMetaBitsLo      = 8,   // uint64 sum of codeword lengths (words 8 and 9; zero between calls)
-    kMetaClocks      = 16,  // 24 uint64 phase-clock accumulators (only in CMPZ_PHASE_CLOCKS builds)
-    kMetaWords       = 64
-};
-
-struct CompressArgs {
-    const float *x;
-    uint8_t     *out;
-    uint64_t     out_cap;
-    uint32_t     numel, H, W, HW;
-    uint32_t     shape[4];
-    uint32_t     radius, sub, guard_shift, eb_bits;
-    float        r;
-    Layout       lay;
-    // context scratch
-    uint16_t *sym;
-    uint32_t *hist;         // zero between calls
-    uint32_t *hist_copy;
-    uint8_t  *lens;
-    uint64_t *codes;        // len << 56 | code
-    uint64_t *desc;         // one descriptor per encode tile, see kDescAgg
-    uint32_t *outl_cnt;     // outliers in each chunk
-    uint32_t  tile_chunks;  // chunks per encode tile: 1, 2, 4 or 8
-    uint32_t *meta;
-    uint32_t *status;
-};
-
-struct DecompressArgs {
-    const uint8_t *buf;
-    uint64_t       size;
-    float         *xout;
-    uint32_t       numel, planes, H, W, HW;
-    uint32_t       shape[4];
-    uint32_t       radius, sub, guard_shift, eb_bits;
-    float          s;
-    Layout         lay;
-    uint32_t *meta;
-    uint32_t *status;
-};
-
-constexpr uint32_t kLB = 11;                      // bits resolved by the first decode table
-struct DecodeTables;                              // cmpz_decode_core.h
-
 // Exact n / d for 32-bit n and d via one 64x32 high multiply (M = ceil(2^64 / d)).
 struct FastDiv {
     uint32_t d, mhi, mlo;
@@ -128,6 +72,123 @@ struct FastDiv {
         return (uint32_t)(t >> 32);
     }
 };
+
+// Section offsets of a container that depend on the element count and the configuration only.
+__host__ __device__ inline Layout make_layout(uint64_t numel, uint32_t radius, uint32_t sub)
+{
+    auto up16 = [](uint64_t v) { return (v + 15) & ~15ull; };
+    Layout l;
+    l.nchunks = (uint32_t)((numel + kChunk - 1) / kChunk);
+    l.nsub = kChunk / sub;
+    l.off_lens = kHeaderBytes;
+    l.off_chunk_off = l.off_lens + up16(2ull * radius);
+    l.off_outl_off = l.off_chunk_off + up16(4ull * ((uint64_t)l.nchunks + 1));
+    l.off_sub_bits = l.off_outl_off + up16(4ull * ((uint64_t)l.nchunks + 1));
+    l.off_payload = l.off_sub_bits + up16(2ull * (uint64_t)l.nchunks * l.nsub);
+    return l;
+}
+
+// Scratch words in ctx->d_meta (decompression side).
+enum MetaWord : int {
+    kMetaBad         = 4,   // decompress: nonzero when the container failed validation
+    kMetaWords       = 64
+};
+
+// ---- compression: one call handles a batch of tensors, every stage is one launch ----
+//
+// Chunks of all tensors of a call are numbered consecutively (tensor t owns the global chunks
+// chunk_base .. chunk_base + nchunks - 1); the symbol scratch holds whole chunks, so tensor t's
+// symbols start at element chunk_base * 4096.  The bit-count and packing kernels give a workgroup
+// a range of kPackChunks consecutive chunks of one tensor; those ranges are numbered
+// consecutively too (tensor t owns pack_base .. ).
+constexpr int      kBatchMax   = 24;        // tensors per launch group (kernel arguments hold their descriptors)
+constexpr uint32_t kPackChunks = 16;        // chunks per workgroup of the bit-count and packing kernels
+
+struct TensorC {
+    const float *x;
+    uint8_t     *out;
+    uint64_t     out_cap;
+    uint32_t     shape[4];
+    uint32_t     numel, nchunks, chunk_base, eb_bits;
+    float        r;
+    uint32_t     sweep_base;    // first workgroup of this tensor in the first sweep
+    uint32_t     pack_base;     // first chunk range of this tensor
+    FastDiv      divW, divHW;
+};
+
+// Per tensor slot, written by the kernels of a call; range_events is zero between calls.
+struct TensorMeta {
+    uint32_t range_events;      // elements clamped by the pre-quantisation
+    uint32_t max_len;           // longest codeword
+    uint32_t skip;              // the container does not fit: nothing but the header is written
+    uint32_t n_outliers;
+    uint32_t total_units;       // payload size in 16-byte units
+    uint32_t pad;
+    uint64_t total_bits;
+};
+
+struct BatchC {
+    uint32_t n;                 // tensors of this launch group
+    uint32_t radius, sub, guard_shift;
+    uint32_t sweep_chunks;      // chunks per workgroup in the first sweep
+    uint32_t sweep_wgs, pack_wgs, total_chunks;
+    // context scratch
+    uint16_t   *sym;            // whole chunks
+    uint32_t   *hist;           // [slot][kHistCopies][kMaxSym], zero between calls
+    uint32_t   *hist_copy;      // [slot][kMaxSym]
+    uint8_t    *lens;           // [slot][kMaxSym]
+    uint64_t   *codes;          // [slot][kMaxSym]: len << 56 | code
+    uint32_t   *enc32;          // [slot][kMaxSym]: code << (32 - len) | len, valid while max_len <= 27
+    uint32_t   *outl_cnt;       // [global chunk]: outliers
+    uint32_t   *chunk_bits;     // [global chunk]: sum of codeword lengths
+    uint32_t   *range_units;    // [chunk range]: payload units, later their exclusive prefix within the tensor
+    uint32_t   *range_outl;     // [chunk range]: outliers, later their exclusive prefix within the tensor
+    uint32_t   *range_bits;     // [chunk range]: sum of codeword lengths
+    TensorMeta *tmeta;          // [slot]
+    uint32_t   *status;
+    TensorC     t[kBatchMax];
+};
+
+struct DecompressArgs {
+    const uint8_t *buf;
+    uint64_t       size;
+    float         *xout;
+    uint32_t       numel, planes, H, W, HW;
+    uint32_t       shape[4];
+    uint32_t       radius, sub, guard_shift, eb_bits;
+    float          s;
+    Layout         lay;
+    uint32_t *meta;
+    uint32_t *status;
+};
+
+constexpr uint32_t kLB = 11;                      // bits resolved by the first decode table
+struct DecodeTables;                              // cmpz_decode_core.h
+
+// Pre-quantisation of one value (Section 3.1, first stage): one fp32 multiply, clamp to +-16384
+// (NaN -> 0), round half to even (v_rndne_f32).
+__device__ __forceinline__ int quant(float x, float r)
+{
+    float t = x * r;
+    if (!(fabsf(t) <= (float)kQMax)) t = (t != t) ? 0.0f : copysignf((float)kQMax, t);
+    return (int)__builtin_rintf(t);
+}
+// 1 if the pre-quantisation clamps this value (it lies outside the quantiser's range or is not finite)
+__device__ __forceinline__ uint32_t clamps(float x, float r)
+{
+    const float t = x * r;
+    return (fabsf(t) <= (float)kQMax) ? 0u : 1u;
+}
+// Lorenzo residual of element i at plane coordinates (h, w), from x alone.
+__device__ __forceinline__ int delta_from_x(const float *__restrict__ x, uint32_t i, uint32_t h, uint32_t w,
+                                            uint32_t W, float r)
+{
+    const int q = quant(x[i], r);
+    const int left = (w > 0) ? quant(x[i - 1], r) : 0;
+    const int up = (h > 0) ? quant(x[i - W], r) : 0;
+    const int diag = (h > 0 && w > 0) ? quant(x[i - W - 1], r) : 0;
+    return q - left - up + diag;
+}
 
 // --- wave-level scans on the DPP network (row shifts inside 16-lane rows, then the two
 // row broadcasts that CDNA keeps from GCN); no LDS traffic, unlike __shfl_up ---------------
@@ -195,7 +256,7 @@ __device__ __forceinline__ uint32_t rank_within_length(uint32_t L, uint32_t (*wa
 
 // Kernel identifiers for the optional per-kernel timing (cmp_profile).
 enum KernelId : int {
-    kKQuantLorenzoHist = 0, kKCodebook, kKEncode, kKOutliers, kKEmpty,
+    kKQuantLorenzoHist = 0, kKCodebook, kKLengths, kKScan, kKPack, kKClear,
     kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKDecodeFusedRest, kKControllerStats,
     kKernelCount
 };
@@ -229,10 +290,14 @@ inline void launch(Profiler *p, int id, K kernel, dim3 grid, dim3 block, hipStre
     }
 }
 
-void launch_compress_begin(const CompressArgs &a, Profiler *prof, hipStream_t st);
-void launch_compress_finish(const CompressArgs &a, Profiler *prof, hipStream_t st);
-void launch_codebook(const CompressArgs &a, Profiler *prof, hipStream_t st);
-bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st);
+// Compression stages, each one launch over all tensors of the group (cmpz_sweep1.hip,
+// cmpz_compress.hip, cmpz_codebook.hip, cmpz_pack.hip).
+void launch_sweep1(const BatchC &b, Profiler *prof, hipStream_t st);
+void launch_sweep1_untiled(const BatchC &b, uint32_t t, Profiler *prof, hipStream_t st);
+bool sweep1_tiled_fits(uint32_t W);
+void launch_codebook(const BatchC &b, Profiler *prof, hipStream_t st);
+void launch_pack(const BatchC &b, Profiler *prof, hipStream_t st);
+void launch_clear(const BatchC &b, Profiler *prof, hipStream_t st);
 size_t decode_tables_bytes();
 void launch_decompress(const DecompressArgs &a, void *tables, uint32_t *items, const volatile uint32_t *hint_host,
                        uint32_t *hint_dev, Profiler *prof, hipStream_t st);

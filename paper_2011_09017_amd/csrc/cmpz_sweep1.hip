@@ -19,24 +19,7 @@ constexpr int kThreads = 256;
 constexpr int kHalo    = 1040;                    // LDS slots in front of the chunk; needs W + 4 <= kHalo
 constexpr int kQWords  = kHalo + (int)kChunk + 16;
 
-__device__ __forceinline__ int quant(float x, float r)
-{
-    float t = x * r;
-    if (!(fabsf(t) <= (float)kQMax)) t = (t != t) ? 0.0f : copysignf((float)kQMax, t);
-    return (int)__builtin_rintf(t);
-}
-__device__ __forceinline__ uint32_t clamps(float x, float r)
-{
-    const float t = x * r;
-    return (fabsf(t) <= (float)kQMax) ? 0u : 1u;
-}
-
-struct Sweep1Plan {
-    FastDiv  divW, divHW;
-    uint32_t chunks_per_wg;
-};
-
-__global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(CompressArgs a, Sweep1Plan pl)
+__global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(BatchC b)
 {
     __shared__ __align__(16) int16_t Q[kQWords];
     __shared__ uint32_t hist[kMaxSym];
@@ -44,15 +27,22 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Com
     const int tid = threadIdx.x, lane = tid & 63;
     for (int k = tid; k < (int)kMaxSym; k += kThreads) hist[k] = 0;
 
-    const float *__restrict__ x = a.x;
-    const uint32_t numel = a.numel, W = a.W, H = a.H, HW = a.HW;
-    const int R = (int)a.radius;
-    const float r = a.r;
+    // the tensor this workgroup works on (uniform: scalar loads from the kernel arguments)
+    uint32_t ti = 0;
+    for (uint32_t k = 1; k < b.n; ++k) if (blockIdx.x >= b.t[k].sweep_base) ti = k;
+    const TensorC &tc = b.t[ti];
+    const uint32_t wg = blockIdx.x - tc.sweep_base;
+    const float *__restrict__ x = tc.x;
+    const uint32_t numel = tc.numel, H = tc.shape[2], W = tc.shape[3], HW = H * W, nchunks = tc.nchunks;
+    const FastDiv divW = tc.divW, divHW = tc.divHW;
+    uint16_t *__restrict__ sym = b.sym + (uint64_t)tc.chunk_base * kChunk;
+    const int R = (int)b.radius;
+    const float r = tc.r;
     uint32_t events = 0, zero_run = 0;            // clamped elements; symbols equal to R seen by this thread
 
-    for (uint32_t t = 0; t < pl.chunks_per_wg; ++t) {
-        const uint32_t c = blockIdx.x * pl.chunks_per_wg + t;
-        if (c >= a.lay.nchunks) break;
+    for (uint32_t t = 0; t < b.sweep_chunks; ++t) {
+        const uint32_t c = wg * b.sweep_chunks + t;
+        if (c >= nchunks) break;
         const uint32_t t0 = c * kChunk;                              // first element of the chunk
         const uint32_t t1 = (numel - t0 < kChunk) ? numel : t0 + kChunk;
         __syncthreads();                                             // previous chunk's phase B is done with Q
@@ -93,9 +83,9 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Com
         if (g0 < t1) {
             // plane coordinates of the first element, then bit masks over the 16 elements:
             // mw bit j = element j starts a row, mh bit j = element j lies in row 0 of its plane
-            const uint32_t p = pl.divHW.div(g0);
+            const uint32_t p = divHW.div(g0);
             const uint32_t rem = g0 - p * HW;
-            uint32_t h = pl.divW.div(rem);
+            uint32_t h = divW.div(rem);
             const uint32_t w = rem - h * W;
             uint32_t mw = 0, mh = 0;
             uint32_t j = w ? W - w : 0u;                             // first row start at or after element 0
@@ -144,18 +134,15 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Com
                 uint4 o0, o1;
                 o0.x = s[0] | (s[1] << 16); o0.y = s[2] | (s[3] << 16); o0.z = s[4] | (s[5] << 16); o0.w = s[6] | (s[7] << 16);
                 o1.x = s[8] | (s[9] << 16); o1.y = s[10] | (s[11] << 16); o1.z = s[12] | (s[13] << 16); o1.w = s[14] | (s[15] << 16);
-                *reinterpret_cast<uint4 *>(a.sym + g0) = o0;
-                *reinterpret_cast<uint4 *>(a.sym + g0 + 8) = o1;
+                *reinterpret_cast<uint4 *>(sym + g0) = o0;
+                *reinterpret_cast<uint4 *>(sym + g0 + 8) = o1;
             } else {
-                for (uint32_t k = 0; k < nval; ++k) a.sym[g0 + k] = (uint16_t)s[k];
+                for (uint32_t k = 0; k < nval; ++k) sym[g0 + k] = (uint16_t)s[k];
             }
         }
         if (nout) atomicAdd(&ocnt, nout);
         __syncthreads();
-        if (tid == 0) {
-            a.outl_cnt[c] = ocnt;
-            if (c % a.tile_chunks == 0) a.desc[c / a.tile_chunks] = 0;       // re-arm the encode sweep's scan
-        }
+        if (tid == 0) b.outl_cnt[tc.chunk_base + c] = ocnt;
     }
 
     // zero residuals: one LDS atomic per wave
@@ -166,30 +153,24 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Com
     __syncthreads();
     for (int k = tid; k < (int)kMaxSym; k += kThreads) {
         const uint32_t n = hist[k];
-        if (n) atomicAdd(&a.hist[(blockIdx.x % kHistCopies) * kMaxSym + k], n);
+        if (n) atomicAdd(&b.hist[((uint64_t)ti * kHistCopies + wg % kHistCopies) * kMaxSym + k], n);
     }
     {
         const uint32_t tot = wave_inclusive_sum(events);
-        if (lane == 63 && tot) atomicAdd(&a.meta[kMetaRangeEvents], tot);
+        if (lane == 63 && tot) atomicAdd(&b.tmeta[ti].range_events, tot);
     }
 }
 
 }  // namespace
 
-// Returns false when rows are too wide for the halo (caller uses the untiled kernel).
-bool launch_sweep1_tiled(const CompressArgs &a, Profiler *prof, hipStream_t st)
+// Rows this wide do not fit the halo: such tensors take the untiled kernel.
+bool sweep1_tiled_fits(uint32_t W) { return W + 4 <= (uint32_t)kHalo; }
+
+// One launch over the tensors of the group whose rows fit (their sweep_base ranges).
+void launch_sweep1(const BatchC &b, Profiler *prof, hipStream_t st)
 {
-    if (a.W + 4 > (uint32_t)kHalo) return false;
-    Sweep1Plan pl;
-    pl.divW = FastDiv::make(a.W);
-    pl.divHW = FastDiv::make(a.HW);
-    // every workgroup ends with a flush of its histogram (contended atomics): few, long-lived
-    // workgroups, but still a few per CU
-    pl.chunks_per_wg = (a.lay.nchunks + 2047) / 2048;
-    if (pl.chunks_per_wg < 1) pl.chunks_per_wg = 1;
-    const uint32_t grid = (a.lay.nchunks + pl.chunks_per_wg - 1) / pl.chunks_per_wg;
-    launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist_tiled, dim3(grid), dim3(kThreads), st, a, pl);
-    return true;
+    if (b.sweep_wgs == 0) return;
+    launch(prof, kKQuantLorenzoHist, k_quant_lorenzo_split_hist_tiled, dim3(b.sweep_wgs), dim3(kThreads), st, b);
 }
 
 }  // namespace cmpz

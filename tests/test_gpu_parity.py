@@ -55,6 +55,9 @@ def check_case(gpu, orc, x_host: np.ndarray, eb: float, ctx, ocfg, stages=True, 
     oi = got[h["off_outl_idx"]:h["off_outl_idx"] + 4 * h["n_outliers"]].view("<u4")
     ov = got[h["off_outl_val"]:h["off_outl_val"] + 4 * h["n_outliers"]].view("<i4")
     assert np.array_equal(oi, ost.outl_idx) and np.array_equal(ov, ost.outl_val)
+    if stages:
+        assert np.array_equal(ctx.stage(gpu.CMP_STAGE_OUTLIER_IDX).numpy().view(np.uint32), ost.outl_idx)
+        assert np.array_equal(ctx.stage(gpu.CMP_STAGE_OUTLIER_VAL).numpy().view(np.int32), ost.outl_val)
     # decompress
     y = ctx.decompress(buf, size, shape, eb)
     assert ctx.last_status() in (0, gpu.CMP_W_RANGE)
@@ -386,3 +389,60 @@ def test_config5_shapes_full_size_bit_exact(gpu, orc, name, ti):
     ctx = make_ctx(gpu, max_numel=n, sub=32)
     x = wl.tensor(ti, device="cuda")
     full_size_case(gpu, orc, ctx, x, wl.ebs[0], 32, f"{name}[{ti}] {shape}")
+
+
+def test_batch_equals_single_calls_equals_oracle(gpu, orc):
+    """cmp_compress_batch: container i is what cmp_compress gives for tensor i, and what the oracle
+    gives; tensors of different shapes, error bounds and outlier content, an empty one, wide rows
+    (the untiled first sweep) and more tensors than one launch group holds."""
+    sub = 32
+    ocfg = orc.Config(sub=sub)
+    shapes = [(2, 8, 56, 56), (3, 16, 28, 28), (4, 32, 14, 14), (8, 64, 7, 7), (1, 2, 112, 112), (0, 3, 5, 5),
+              (1, 1, 3, 2000), (1, 1, 1, 1), (2, 3, 55, 55)]
+    shapes = shapes + [(1, 4, 9 + k, 11 + k) for k in range(20)]          # 29 tensors: two launch groups
+    ebs = [1e-2, 5e-3, 1e-2, 1e-1, 1e-3, 1e-2, 1e-2, 1e-2, 1e-3] + [1e-2] * 20
+    xs = []
+    for k, shape in enumerate(shapes):
+        if int(np.prod(shape)) > 1:
+            x = activation(shape, 5, 0.5, seed=900 + k).numpy()
+        else:
+            x = np.full(shape, 0.5, np.float32)
+        if k % 3 == 1 and x.size:
+            x.reshape(-1)[x.size // 2] = 25000.0 * ebs[k]                 # an outlier cluster, inside the quantiser's range
+        xs.append(torch.from_numpy(x).cuda())
+    total = sum(x.numel() for x in xs)
+    ctx = make_ctx(gpu, sub=sub, max_numel=total)
+    single = make_ctx(gpu, sub=sub, max_numel=max(x.numel() for x in xs))
+    for rep in range(2):                                                  # the scratch is clean after a call
+        outs, sizes, rc = ctx.compress_batch(xs, ebs)
+        assert rc == 0
+        for x, eb, out, size in zip(xs, ebs, outs, sizes):
+            ref, rsize, rrc = single.compress(x, eb)
+            assert rrc == 0 and rsize == size
+            assert torch.equal(out[:size], ref[:rsize])
+            orc_rc, obuf, osize, _ = orc.compress(x.cpu().numpy(), eb, ocfg)
+            assert orc_rc == 0 and osize == size
+            assert np.array_equal(out[:size].cpu().numpy(), obuf)
+            y = single.decompress(out, size, x.shape, eb)
+            assert single.last_status() == 0
+            orc_rc, oy = orc.decompress(obuf, x.shape, eb, ocfg)
+            assert np.array_equal(y.cpu().numpy().view(np.uint32), oy.view(np.uint32))
+    # a context smaller than the batch works it off in several groups
+    small = make_ctx(gpu, sub=sub, max_numel=max(x.numel() for x in xs))
+    outs2, sizes2, rc = small.compress_batch(xs, ebs)
+    assert rc == 0 and sizes2 == sizes
+    for a, b, n in zip(outs, outs2, sizes):
+        assert torch.equal(a[:n], b[:n])
+    # one container too small: reported, the others are complete; capacity below the fixed sections: refused
+    caps = [o.numel() for o in outs]
+    tight = [torch.empty(sizes[k] - 16 if k == 4 else caps[k], dtype=torch.uint8, device="cuda") for k in range(len(xs))]
+    _, sizes3, rc = ctx.compress_batch(xs, ebs, outs=tight)
+    assert rc == gpu.CMP_E_NOSPACE and sizes3 == sizes
+    assert ctx.last_status() == gpu.CMP_E_NOSPACE
+    for k in (0, 3, 8, 28):
+        assert torch.equal(tight[k][:sizes[k]], outs[k][:sizes[k]])
+    tight[2] = torch.empty(64, dtype=torch.uint8, device="cuda")
+    _, _, rc = ctx.compress_batch(xs, ebs, outs=tight)
+    assert rc == gpu.CMP_E_NOSPACE
+    outs4, sizes4, rc = ctx.compress_batch(xs, ebs)                         # and the context is still clean
+    assert rc == 0 and sizes4 == sizes and torch.equal(outs4[4][:sizes[4]], outs[4][:sizes[4]])
