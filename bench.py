@@ -68,13 +68,17 @@ MEASURED_TRAFFIC = {
 class Run:
     """One workload resident on the GPU: inputs, containers, outputs, contexts."""
 
-    def __init__(self, binding, torch, wl, eb, sub, nstreams, dev):
+    def __init__(self, binding, torch, wl, eb, sub, nstreams, dev, api="batch"):
         self.b, self.torch, self.wl, self.eb, self.sub = binding, torch, wl, eb, sub
+        self.api = api if nstreams == 1 else "single"          # batches are one call on one stream
         self.xs = [wl.tensor(i, device=dev) for i in range(len(wl.shapes))]
         self.numels = [x.numel() for x in self.xs]
         self.total = sum(self.numels)
         S = self.S = max(1, min(nstreams, len(self.xs)))
-        self.ctxs = [binding.Context(sub=sub, max_numel=max(self.numels[k::S])) for k in range(S)]
+        if self.api == "batch":
+            self.ctxs = [binding.Context(sub=sub, max_numel=self.total)]
+        else:
+            self.ctxs = [binding.Context(sub=sub, max_numel=max(self.numels[k::S])) for k in range(S)]
         self.bounds = [self.ctxs[0].bound(x.shape) for x in self.xs]
         self.arena = [torch.empty(b, dtype=torch.uint8, device=dev) for b in self.bounds]
         self.outs = [torch.empty_like(x) for x in self.xs]
@@ -83,8 +87,14 @@ class Run:
         self.streams = [t.cuda_stream for t in self.tstreams]
         self.order = list(range(len(self.xs)))
 
-    def compress_all(self):
+    def compress_all(self, stream=None):
         b, S = self.b, self.S
+        if self.api == "batch":
+            rc, _ = b.cmp_compress_batch(self.ctxs[0]._h, [x.data_ptr() for x in self.xs], [x.shape for x in self.xs],
+                                         [self.eb] * len(self.xs), [a.data_ptr() for a in self.arena],
+                                         [a.numel() for a in self.arena], False, self.streams[0])
+            assert rc == 0, b.cmp_strerror(rc)
+            return
         for i in self.order:
             x, buf = self.xs[i], self.arena[i]
             rc, _ = b.cmp_compress(self.ctxs[i % S]._h, x.data_ptr(), x.shape, self.eb, buf.data_ptr(), buf.numel(),
@@ -93,6 +103,13 @@ class Run:
 
     def decompress_all(self):
         b, S = self.b, self.S
+        if self.api == "batch":
+            rev = list(reversed(self.order))
+            rc = b.cmp_decompress_batch(self.ctxs[0]._h, [self.arena[i].data_ptr() for i in rev],
+                                        [self.bounds[i] for i in rev], [self.xs[i].shape for i in rev],
+                                        [self.eb] * len(rev), [self.outs[i].data_ptr() for i in rev], self.streams[0])
+            assert rc == 0, b.cmp_strerror(rc)
+            return
         for i in reversed(self.order):
             rc = b.cmp_decompress(self.ctxs[i % S]._h, self.arena[i].data_ptr(), self.bounds[i], self.xs[i].shape,
                                   self.eb, self.outs[i].data_ptr(), self.streams[i % S])
@@ -150,11 +167,15 @@ class Run:
         S0 = self.streams[0]
         b = self.b
         for _ in range(steps):
-            for i in self.order:
+            if self.api == "batch":
+                self.compress_all()
+            for i in (self.order if self.api != "batch" else []):
                 rc, _ = b.cmp_compress(self.ctxs[i % self.S]._h, self.xs[i].data_ptr(), self.xs[i].shape, self.eb,
                                        self.arena[i].data_ptr(), self.arena[i].numel(), False, S0)
                 assert rc == 0, b.cmp_strerror(rc)
-            for i in reversed(self.order):
+            if self.api == "batch":
+                self.decompress_all()
+            for i in (reversed(self.order) if self.api != "batch" else []):
                 rc = b.cmp_decompress(self.ctxs[i % self.S]._h, self.arena[i].data_ptr(), self.bounds[i],
                                       self.xs[i].shape, self.eb, self.outs[i].data_ptr(), S0)
                 assert rc == 0, b.cmp_strerror(rc)
@@ -196,6 +217,9 @@ def main() -> int:
     ap.add_argument("--streams", type=int, default=1,
                     help="streams of the headline schedule (the benchmark configuration says one)")
     ap.add_argument("--extra-streams", type=int, default=6, help="streams of the `multi_stream` extra (0 = skip)")
+    ap.add_argument("--api", default="batch", choices=["batch", "single"],
+                    help="batch: one cmp_compress_batch call per step (one launch per stage over all tensors); "
+                         "single: one cmp_compress call per tensor")
     ap.add_argument("--no-extras", action="store_true", help="skip sparse_variant and other_configs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -219,7 +243,7 @@ def main() -> int:
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
 
-    run = Run(binding, torch, wl, eb, args.sub, args.streams, dev)
+    run = Run(binding, torch, wl, eb, args.sub, args.streams, dev, args.api)
     for _ in range(args.warmup):
         run.step()
     run.check()
@@ -283,7 +307,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32 quantiser, i32/bit codec", "data": "synthetic",
         "config": {"workload": wl.name, "tensors": len(run.xs), "numel": total, "eb": eb, "radius": 512,
-                   "chunk": 4096, "sub": args.sub, "streams": run.S, "schedule": "compress all in forward order, "
+                   "chunk": 4096, "sub": args.sub, "streams": run.S, "api": run.api, "schedule": "compress all in forward order, "
                    "then decompress all in reverse order", "p_zero": wl.p_zero, "box_k": wl.k,
                    "seed_base": wl.seed(0)},
         "compression_ratio": head["compression_ratio"],
@@ -333,7 +357,7 @@ def main() -> int:
 
     # ---- extras ------------------------------------------------------------------------
     def measure(wl2, eb2, nstreams):
-        r = Run(binding, torch, wl2, eb2, args.sub, nstreams, dev)
+        r = Run(binding, torch, wl2, eb2, args.sub, nstreams, dev, args.api)
         for _ in range(args.warmup):
             r.step()
         r.check()

@@ -81,15 +81,15 @@ typedef struct {
     uint32_t chunk;        /* codes per independently addressable Huffman chunk; 4096          */
     uint32_t sub;          /* codes per sub-block whose bit count is stored: 32, 64 or 128    */
     uint32_t guard_shift;  /* 1..23, see "Arithmetic" above                                    */
-    uint64_t max_numel;    /* largest tensor this context will be asked to handle              */
+    uint64_t max_numel;    /* most elements one launch group holds: no tensor may be larger, and a
+                              batch with more in total is worked off in several groups         */
 } cmp_config;
 
 /* Defaults: radius 512, chunk 4096, sub 128, guard_shift 7, max_numel 2^28. */
 void cmp_default_config(cmp_config *cfg);
 
 /* Create a context on GPU `device` and allocate its scratch (about
- * 2 bytes * max_numel + 16 bytes per chunk of device memory, and 64 bytes of
- * pinned host memory that the decompression kernels report to).  cfg == NULL
+ * 2 bytes * max_numel + 9 bytes per chunk + 1.3 MB of device memory).  cfg == NULL
  * means defaults. */
 int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device);
 void cmp_destroy(cmp_ctx *ctx);
@@ -153,6 +153,13 @@ int cmp_compressed_size(cmp_ctx *ctx, const void *d_buf, size_t *h_size, void *s
  * (never written out of bounds) and is reported by cmp_last_status. */
 int cmp_decompress(cmp_ctx *ctx, const void *d_buf, size_t size, const int64_t shape[4],
                    float eb, float *d_xout, void *stream);
+
+/* cmp_decompress for n containers at once (host arrays of n entries, as for cmp_compress_batch):
+ * one kernel launch decodes all of them; tensor i comes out bit for bit as cmp_decompress gives
+ * it.  Arguments are checked for all containers before anything is launched.  Asynchronous; the
+ * most severe condition over the containers is reported by cmp_last_status. */
+int cmp_decompress_batch(cmp_ctx *ctx, int n, const void *const *d_buf, const size_t *size, const int64_t (*shapes)[4],
+                         const float *eb, float *const *d_xout, void *stream);
 
 /* Waits for `stream` and returns, then clears, the most severe condition the
  * GPU recorded for this context since the last query: a negative error code, else

@@ -23,7 +23,7 @@ CMP_STAGE_OUTLIER_IDX, CMP_STAGE_OUTLIER_VAL = 4, 5
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
            "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",
            "cmp_profile", "cmp_profile_read", "cmp_default_controller_config", "cmp_estimate_eb",
-           "cmp_compress_begin", "cmp_compress_finish", "cmp_compress_batch"]
+           "cmp_compress_begin", "cmp_compress_finish", "cmp_compress_batch", "cmp_decompress_batch"]
 
 
 class cmp_controller_config(C.Structure):
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.cmp_debug_stage.argtypes = [vp, i32, vp, vp]; L.cmp_debug_stage.restype = i32
         L.cmp_strerror.argtypes = [i32]; L.cmp_strerror.restype = C.c_char_p
         L.cmp_compress_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]; L.cmp_compress_batch.restype = i32
+        L.cmp_decompress_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]; L.cmp_decompress_batch.restype = i32
         L.cmp_compress_begin.argtypes = [vp, vp, vp, C.c_float, vp]; L.cmp_compress_begin.restype = i32
         L.cmp_compress_finish.argtypes = [vp, vp, sz, vp, vp]; L.cmp_compress_finish.restype = i32
         L.cmp_default_controller_config.argtypes = [vp]; L.cmp_default_controller_config.restype = None
@@ -140,6 +141,17 @@ def cmp_compress_finish(ctx, d_out: int, out_cap: int, want_size: bool, stream: 
 def cmp_decompress(ctx, d_buf: int, size: int, shape, eb: float, d_xout: int, stream: int) -> int:
     s = _shape4(shape)
     return lib().cmp_decompress(ctx, d_buf, size, C.addressof(s), C.c_float(eb), d_xout, stream)
+
+
+def cmp_decompress_batch(ctx, d_bufs, sizes, shapes, ebs, d_xouts, stream: int) -> int:
+    n = len(d_bufs)
+    assert len(sizes) == n and len(shapes) == n and len(ebs) == n and len(d_xouts) == n
+    bufs = (C.c_void_p * n)(*d_bufs)
+    outs = (C.c_void_p * n)(*d_xouts)
+    sz = (C.c_size_t * n)(*sizes)
+    sh = (C.c_int64 * (4 * n))(*[int(v) for s in shapes for v in s])
+    eb = (C.c_float * n)(*ebs)
+    return lib().cmp_decompress_batch(ctx, n, bufs, sz, sh, eb, outs, stream)
 
 
 def cmp_last_status(ctx, stream: int) -> int:
@@ -248,6 +260,16 @@ class Context:
         if rc != CMP_OK:
             raise CmpError(rc, "cmp_decompress")
         return out
+
+    def decompress_batch(self, bufs, sizes, shapes, ebs, outs=None):
+        """Several containers in one call.  Returns the list of reconstructed tensors."""
+        if outs is None:
+            outs = [torch.empty(tuple(s), dtype=torch.float32, device=b.device) for b, s in zip(bufs, shapes)]
+        rc = cmp_decompress_batch(self._h, [b.data_ptr() for b in bufs], list(sizes), list(shapes), list(ebs),
+                                  [o.data_ptr() for o in outs], self._stream())
+        if rc != CMP_OK:
+            raise CmpError(rc, "cmp_decompress_batch")
+        return outs
 
     def estimate_eb(self, act: torch.Tensor, loss: torch.Tensor, mom: torch.Tensor, sigma_frac=0.01, a=0.32,
                     eb_min=1e-6, eb_max=1.0):

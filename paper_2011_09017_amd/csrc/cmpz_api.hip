@@ -12,7 +12,7 @@ namespace cmpz {
 const char *const kKernelNames[kKernelCount] = {
     "k_quant_lorenzo_split_hist", "k_codebook", "k_lengths", "k_scan",
     "k_pack", "k_clear", "k_decode_tables", "k_decode", "k_patch_outliers", "k_row_scan",
-    "k_col_scan_dequant", "k_decode_fused", "k_decode_fused_rest", "k_controller_stats"};
+    "k_col_scan_dequant", "k_decode_fused", "k_controller_stats"};
 }  // namespace cmpz
 
 using namespace cmpz;
@@ -28,7 +28,6 @@ struct Scratch {
     // decompression
     uint32_t   *meta;
     void       *tables;
-    uint32_t   *items;          // item list of the fused decode kernels
     ControllerScratch *ctl;
     ControllerResult  *ctl_result;
     uint64_t    max_chunks;     // chunks the symbol scratch holds
@@ -40,8 +39,6 @@ struct cmp_ctx {
     int        device;
     uint8_t   *d_base;          // one allocation, carved up into `s`
     Scratch    s;
-    uint32_t  *h_hint;          // pinned host word the decode kernels report to (see launch_decode_fused)
-    uint32_t  *d_hint;          // its device address
     uint64_t   last_numel;      // first tensor of the latest compress call (cmp_debug_stage)
     const uint8_t *last_out;
     BatchC     pending;         // what cmp_compress_begin left for cmp_compress_finish
@@ -117,7 +114,6 @@ uint64_t carve_scratch(Scratch *sc, uint8_t *base, uint64_t max_numel, uint64_t 
     s.status = reinterpret_cast<uint32_t *>(carve(4));
     s.meta = reinterpret_cast<uint32_t *>(carve(4 * kMetaWords));
     s.tables = carve(decode_tables_bytes());
-    s.items = reinterpret_cast<uint32_t *>(carve(4 * fused_item_words(max_numel)));
     s.ctl = reinterpret_cast<ControllerScratch *>(carve(sizeof(ControllerScratch)));
     s.ctl_result = reinterpret_cast<ControllerResult *>(carve(sizeof(ControllerResult)));
     if (sc) *sc = s;
@@ -186,13 +182,6 @@ int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
         (void)hipFree(ctx->d_base); delete ctx; return CMP_E_HIP;
     }
     carve_scratch(&ctx->s, ctx->d_base, c.max_numel, nullptr);
-    ctx->h_hint = nullptr; ctx->d_hint = nullptr;
-    if (hipHostMalloc(reinterpret_cast<void **>(&ctx->h_hint), 64, hipHostMallocMapped) != hipSuccess ||
-        hipHostGetDevicePointer(reinterpret_cast<void **>(&ctx->d_hint), ctx->h_hint, 0) != hipSuccess) {
-        if (ctx->h_hint) (void)hipHostFree(ctx->h_hint);
-        (void)hipFree(ctx->d_base); delete ctx; return CMP_E_HIP;
-    }
-    *ctx->h_hint = 1;                                  // nothing known yet: assume listed items
     *out = ctx;
     return CMP_OK;
 }
@@ -203,7 +192,6 @@ void cmp_destroy(cmp_ctx *ctx)
     DeviceGuard guard(ctx->device);
     (void)hipDeviceSynchronize();
     for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
-    if (ctx->h_hint) (void)hipHostFree(ctx->h_hint);
     (void)hipFree(ctx->d_base);
     delete ctx;
 }
@@ -429,38 +417,56 @@ int cmp_compressed_size(cmp_ctx *ctx, const void *d_buf, size_t *h_size, void *s
     return CMP_OK;
 }
 
+int cmp_decompress_batch(cmp_ctx *ctx, int n, const void *const *d_buf, const size_t *size, const int64_t (*shapes)[4],
+                         const float *eb, float *const *d_xout, void *stream)
+{
+    if (!ctx || n < 0 || (n > 0 && (!d_buf || !size || !shapes || !eb || !d_xout))) return CMP_E_ARG;
+    // every argument is checked before anything is launched
+    std::vector<TensorD> td((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        uint64_t numel;
+        float s, r;
+        if (!d_buf[i] || !shape_numel(shapes[i], &numel)) return CMP_E_ARG;
+        if (numel > ctx->cfg.max_numel || (numel > 0 && !d_xout[i])) return CMP_E_ARG;
+        if (!constants(eb[i], ctx->cfg.guard_shift, &s, &r)) return CMP_E_ARG;
+        if ((reinterpret_cast<uintptr_t>(d_buf[i]) & 15) || (reinterpret_cast<uintptr_t>(d_xout[i]) & 15)) return CMP_E_ARG;
+        if (size[i] < make_layout(numel, ctx->cfg).off_payload) return CMP_E_FORMAT;   // cannot even hold the fixed sections
+        TensorD &t = td[(size_t)i];
+        std::memset(&t, 0, sizeof(t));
+        t.buf = static_cast<const uint8_t *>(d_buf[i]);
+        t.size = size[i];
+        t.xout = d_xout[i];
+        for (int k = 0; k < 4; ++k) t.shape[k] = (uint32_t)shapes[i][k];
+        t.numel = (uint32_t)numel;
+        std::memcpy(&t.eb_bits, &eb[i], 4);
+        t.s = s;
+        if (!plan_decode_fused(&t, ctx->cfg.sub)) t.nitems = 0;
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    for (int i0 = 0; i0 < n; i0 += kBatchMax) {
+        BatchD b;
+        std::memset(&b, 0, sizeof(b));
+        b.radius = ctx->cfg.radius; b.sub = ctx->cfg.sub; b.guard_shift = ctx->cfg.guard_shift;
+        b.meta = ctx->s.meta; b.status = ctx->s.status;
+        for (int i = i0; i < n && i < i0 + kBatchMax; ++i) b.t[b.n++] = td[(size_t)i];
+        launch_decode_fused(b, &ctx->prof, st);
+        // shapes the fused kernel does not take, and empty tensors: one at a time
+        for (uint32_t k = 0; k < b.n; ++k)
+            if (!b.t[k].nitems) launch_decompress_unfused(decompress_args(b, b.t[k]), ctx->s.tables, &ctx->prof, st);
+    }
+    if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
+    return CMP_OK;
+}
+
 int cmp_decompress(cmp_ctx *ctx, const void *d_buf, size_t size, const int64_t shape[4], float eb,
                    float *d_xout, void *stream)
 {
-    uint64_t numel;
-    float s, r;
-    if (!ctx || !d_buf || !shape_numel(shape, &numel)) return CMP_E_ARG;
-    if (numel > ctx->cfg.max_numel || (numel > 0 && !d_xout)) return CMP_E_ARG;
-    if (!constants(eb, ctx->cfg.guard_shift, &s, &r)) return CMP_E_ARG;
-    if ((reinterpret_cast<uintptr_t>(d_buf) & 15) || (reinterpret_cast<uintptr_t>(d_xout) & 15)) return CMP_E_ARG;
-
-    DecompressArgs a;
-    std::memset(&a, 0, sizeof(a));
-    a.lay = make_layout(numel, ctx->cfg);
-    if (size < a.lay.off_payload) return CMP_E_FORMAT;       // cannot even hold the fixed sections
-    a.buf = static_cast<const uint8_t *>(d_buf);
-    a.size = size;
-    a.xout = d_xout;
-    a.numel = (uint32_t)numel;
-    a.planes = (uint32_t)(shape[0] * shape[1]);
-    a.H = (uint32_t)shape[2]; a.W = (uint32_t)shape[3]; a.HW = a.H * a.W;
-    for (int i = 0; i < 4; ++i) a.shape[i] = (uint32_t)shape[i];
-    a.radius = ctx->cfg.radius; a.sub = ctx->cfg.sub; a.guard_shift = ctx->cfg.guard_shift;
-    std::memcpy(&a.eb_bits, &eb, 4);
-    a.s = s;
-    a.meta = ctx->s.meta; a.status = ctx->s.status;
-
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return CMP_E_HIP;
-    launch_decompress(a, ctx->s.tables, ctx->s.items, ctx->h_hint, ctx->d_hint, &ctx->prof,
-                      static_cast<hipStream_t>(stream));
-    if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
-    return CMP_OK;
+    if (!shape) return CMP_E_ARG;
+    const void *bufs[1] = {d_buf};
+    float *outs[1] = {d_xout};
+    return cmp_decompress_batch(ctx, 1, bufs, &size, reinterpret_cast<const int64_t (*)[4]>(shape), &eb, outs, stream);
 }
 
 int cmp_last_status(cmp_ctx *ctx, void *stream)

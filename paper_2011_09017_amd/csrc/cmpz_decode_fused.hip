@@ -14,8 +14,9 @@
 //
 // A band is decoded by one lane per sub-block (the container stores each
 // sub-block's bit count, so every lane knows where its codes start) into an LDS
-// array (int16 in the fast instance of the kernel, int32 in the other: see
-// k_decode_fused).  The band's stretch of the payload is contiguous in the
+// array of int16 (all sums are taken modulo 2^16: the final integers lie within
+// +-16384, so the low 16 bits, sign-extended, are the result whatever the
+// intermediate sums and the outlier residuals reach).  The band's stretch of the payload is contiguous in the
 // container; it is copied into LDS with 128-bit loads first, and the lanes read
 // their codewords from there at arbitrary bit positions (a band whose payload
 // exceeds the staging buffer, more than 8 bits per code on average, is decoded
@@ -51,18 +52,7 @@ struct FusedPlan {
     uint32_t Rb;           // rows per band (big == 1)
     uint32_t nitems;
     FastDiv  divW;
-    uint32_t use_list;     // the int32 kernel walks the listed items only (else: all items)
-    uint32_t *listed_hint; // host-visible word: how many items the latest finished call had listed
-    uint32_t *items;       // items[0]: number of listed items, items[1]: workgroups that are done with
-                           // the list, items[2..]: the listed items
 };
-constexpr uint32_t kItemList = 2;
-
-#ifdef CMPZ_PHASE_CLOCKS
-#define PHASE(k) if (tid == 0) { const long long now_ = clock64(); clk[k] += now_ - last_; last_ = now_; }
-#else
-#define PHASE(k)
-#endif
 
 // LDS written by some lanes of a wave is read by others: the hardware keeps a wave's LDS
 // operations in order, this keeps the compiler from moving them across.
@@ -83,15 +73,13 @@ struct Stage {
     uint32_t nq;           // units staged; 0 = not staged (the band decodes from memory)
 };
 
-// R16 = true: the fast kernel, for sub <= 64.  Residual sums are kept as int16 (a lane's running
-// sum over at most 64 in-range residuals stays below 2^15), which makes room for four workgroups
-// per CU.  It takes the items (planes, groups of small planes) whose chunks hold no outlier and
-// puts the others on a list.  R16 = false: int32 residuals and the outlier path, for that list
-// (pl.use_list) or, for sub = 128, for every item.
-template <int SUB, bool R16>
-__global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(DecompressArgs a, FusedPlan pl)
+// One launch decodes all tensors of a call: a workgroup belongs to one tensor (it validates that
+// container and builds that codebook's decode tables for itself, about a microsecond), its waves
+// take every item_stride-th item of the tensor.
+template <int SUB>
+__global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
 {
-    using RT = typename std::conditional<R16, int16_t, int32_t>::type;
+    using RT = int16_t;
     constexpr int kRows = 8;                              // rows of the column pass in flight together
     constexpr int kLog  = Cfg<SUB>::kLog;
     constexpr int kND   = kBandMax / SUB;                 // decode lanes per band
@@ -105,35 +93,25 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
     __shared__ RT       Rs[kWaves][kBandMax + kND];       // one pad slot per sub-block: lane-conflict free
     __shared__ uint32_t Ps[kWaves][kE * kWave + 2];       // exclusive prefix of sub-block bit counts
     __shared__ __align__(16) uint32_t Ss[kWaves][kStagePad + kStageWords + 4];   // staged payload; after the decode, the lane records
+    static_assert(sizeof(Rs) >= 13 * 1024, "the table build borrows Rs as scratch");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);     // tells the compiler that it is uniform in the wave
-#ifdef CMPZ_PHASE_CLOCKS
-    long long clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    long long last_ = clock64();
-#endif
-    uint32_t n_listed = 0;
-    if (!R16 && pl.use_list) {
-        // nothing listed (the usual case): leave before the tables are built; the last workgroup
-        // to leave, or to finish, re-arms the list
-        n_listed = __hip_atomic_load(pl.items, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (n_listed == 0) {
-            if (tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) { pl.items[1] = 0; *pl.listed_hint = 0; }
-            return;
-        }
-    }
+    // the tensor of this workgroup (uniform: scalar loads from the kernel arguments)
+    uint32_t ti = 0;
+    for (uint32_t k = 1; k < b.n; ++k) if (blockIdx.x >= b.t[k].wg_base) ti = k;
+    const TensorD &td = b.t[ti];
+    const DecompressArgs a = decompress_args(b, td);
+    FusedPlan pl;
+    pl.big = td.big; pl.G = td.G; pl.Rb = td.Rb; pl.nitems = td.nitems; pl.divW = td.divW;
     // every workgroup validates the container and builds the decode tables for itself
     {
         const uint32_t defect = build_tables_256(T, a, reinterpret_cast<uint32_t *>(&Rs[0][0]));
         if (defect) {
-            if (blockIdx.x == 0 && tid == 0) atomicOr(a.status, defect);
-            if (!R16 && pl.use_list && tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) {
-                pl.items[0] = 0; pl.items[1] = 0; *pl.listed_hint = n_listed;
-            }
+            if (blockIdx.x == td.wg_base && tid == 0) atomicOr(a.status, defect);
             return;
         }
     }
-    PHASE(0)
     // ---- from here on the waves are on their own ----
     RT       *R = Rs[wv];
     uint32_t *P = Ps[wv];
@@ -157,7 +135,7 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
     // What a lane fetches ahead for a band: its bit-count entries, its sub-block's chunk bounds,
     // and (uniform) the band's range in the outlier list and the payload bounds of its chunks.
     struct Ahead {
-        uint32_t v[kE], uu0, uu1, olo, ohi, cf, cl, cl1, ilo, ihi;
+        uint32_t v[kE], uu0, uu1, olo, ohi, cf, cl, cl1;
     };
 
     const uint32_t vzero = __builtin_amdgcn_mbcnt_lo(0u, 0u);    // 0, but not known to be uniform
@@ -181,7 +159,7 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
         Ahead f;
 #pragma unroll
         for (int i = 0; i < kE; ++i) f.v[i] = 0;
-        f.uu0 = f.uu1 = f.olo = f.ohi = f.cf = f.cl = f.cl1 = f.ilo = f.ihi = 0;
+        f.uu0 = f.uu1 = f.olo = f.ohi = f.cf = f.cl = f.cl1 = 0;
         if (!g.valid) return f;
         const uint32_t sb0 = g.e0 >> kLog, sb1 = (g.e0 + g.n - 1) >> kLog;
         const uint32_t j0 = sb0 & (kNSub - 1), ent0 = sb0 - j0, nent = j0 + (sb1 - sb0 + 1);
@@ -201,14 +179,6 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
         f.cf = chunk_off[sb0 / kNSub + vzero];
         f.cl = chunk_off[sb1 / kNSub + vzero];
         f.cl1 = chunk_off[sb1 / kNSub + 1 + vzero];
-        if (R16) {
-            // outlier records of all chunks the band's item touches (for a group of small planes
-            // the band is the item)
-            const uint32_t i0 = pl.big ? g.plane0 * HW : g.e0;
-            const uint32_t i1 = pl.big ? i0 + HW - 1 : g.e0 + g.n - 1;
-            f.ilo = outl_off[i0 / kChunk + vzero];
-            f.ihi = outl_off[i1 / kChunk + 1 + vzero];
-        }
         return f;
     };
     // exclusive prefix of a band's bit counts from the start of its first chunk
@@ -249,15 +219,9 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
     };
 
     const uint32_t nbands_big = pl.big ? (H + pl.Rb - 1) / pl.Rb : 1u;
-    const uint32_t item_stride = gridDim.x * kWaves;
-    // the wave's items: every item_stride-th item, or (R16 = false) every item_stride-th listed one
-    auto item_of = [&](uint32_t sl) -> uint32_t {
-        if (R16 || !pl.use_list) return sl;
-        return sl < n_listed ? pl.items[kItemList + sl] : 0xffffffffu;
-    };
-    uint32_t slot = blockIdx.x * kWaves + wv, b = 0;
-    uint32_t item = item_of(slot);
-    Band cur = band_of(item, b);
+    const uint32_t item_stride = td.nwg * kWaves;
+    uint32_t item = (blockIdx.x - td.wg_base) * kWaves + wv, bi = 0;
+    Band cur = band_of(item, bi);
     Ahead fa = fetch(cur);
     int32_t colacc[kColGroups] = {0, 0, 0, 0};               // running column sums (big planes)
     uint4 s0 = make_uint4(0, 0, 0, 0), s1 = s0;
@@ -270,8 +234,8 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
 
     while (cur.valid) {
         // ---- next band: geometry now, bit counts in flight while this band is decoded ----
-        uint32_t nslot = slot, nitem = item, nb = b + 1;
-        if (nb >= nbands_big) { nslot = slot + item_stride; nitem = item_of(nslot); nb = 0; }
+        uint32_t nitem = item, nb = bi + 1;
+        if (nb >= nbands_big) { nitem = item + item_stride; nb = 0; }
         const Band nxt = band_of(nitem, nb);
         const Ahead fn = fetch(nxt);
 
@@ -282,7 +246,7 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
         const uint32_t base = sb0 << kLog;
         const uint32_t u0 = e0 - base;
         const uint32_t j0 = sb0 & (kNSub - 1);           // position of sb0 in its chunk
-        if (b == 0) {
+        if (bi == 0) {
 #pragma unroll
             for (int c = 0; c < kColGroups; ++c) colacc[c] = 0;
         }
@@ -301,21 +265,12 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
             if ((uint32_t)lane + kWave < sg.nq) reinterpret_cast<uint4 *>(S + kStagePad)[lane + kWave] = s1;
         }
         wave_sync();
-        PHASE(1)
 
         // outliers of the band: a range of the outlier list (filtered by index below)
         uint32_t olo = __builtin_amdgcn_readfirstlane(fa.olo), ohi = __builtin_amdgcn_readfirstlane(fa.ohi);
         if (olo > ohi || ohi > n_outl) { bad = true; olo = ohi = 0; }
         // uniform: no outliers, rows are summed while decoding
-        const bool folded = R16 ? true : (olo == ohi);
-        // the fast kernel leaves an item whose chunks hold outliers to the other kernel
-        bool skip = false;
-        if (R16) {
-            skip = __builtin_amdgcn_readfirstlane(fa.ilo) != __builtin_amdgcn_readfirstlane(fa.ihi);
-            if (!skip && olo != ohi) { bad = true; skip = true; }        // the two ranges disagree
-            if (skip && b == 0 && lane == 0) pl.items[kItemList + atomicAdd(pl.items, 1u)] = item;
-        }
-        if (!skip) {
+        const bool folded = olo == ohi;
 
         // ---- decode: one lane per sub-block ----
         int32_t my_tail = 0;
@@ -397,7 +352,6 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
             bad |= lbad;
         }
         wave_sync();                                     // S is free: the lane records take its place
-        PHASE(3)
 
         if (folded) {
             // ---- carries: what each lane's leading elements (before its first row start) lack ----
@@ -434,8 +388,6 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
             }
         }
         wave_sync();
-        }   // !skip
-        PHASE(4)
 
         // ---- next band: bit positions now, its payload in flight during the column pass ----
         Stage sgn = {0, 0};
@@ -444,9 +396,7 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
             sgn = stage_of(nxt, fn);
             stage_load(sgn, s0, s1);
         }
-        PHASE(2)
 
-        if (!skip) {
         // ---- column prefix sums (adding the lanes' carries); wide rows are de-quantised and stored from here ----
         const bool direct = W >= 32;                     // a wave then stores runs of >= 128 bytes
         const uint32_t nrow = pl.big ? rows : H;
@@ -473,7 +423,7 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
 #pragma unroll
                 for (int q = 0; q < kRows; ++q) {
                     acc += t8[q] + ((kk[q] < rc[q].x) ? (int32_t)rc[q].y : 0);
-                    if (kDirect) *reinterpret_cast<float *>(band_out + (off + q * 4u * W)) = (float)acc * s;
+                    if (kDirect) *reinterpret_cast<float *>(band_out + (off + q * 4u * W)) = (float)(int16_t)acc * s;
                     else R[ph[q]] = acc;
                 }
                 u += kRows * W;
@@ -483,7 +433,7 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
                 const uint32_t t = u >> kLog, ph = u + t;
                 const uint2 rc = RC[t];
                 acc += R[ph] + (((u & (uint32_t)(SUB - 1)) < rc.x) ? (int32_t)rc.y : 0);
-                if (kDirect) *reinterpret_cast<float *>(band_out + off) = (float)acc * s; else R[ph] = acc;
+                if (kDirect) *reinterpret_cast<float *>(band_out + off) = (float)(int16_t)acc * s; else R[ph] = acc;
             }
             return acc;
         };
@@ -524,79 +474,63 @@ __global__ __launch_bounds__(kThreads, R16 ? 4 : 3) void k_decode_fused(Decompre
                 }
             }
         }
-        }   // !skip
         wave_sync();                                      // R and the staging buffer are reused by the next band
-        PHASE(5)
-        cur = nxt; fa = fn; sg = sgn; item = nitem; slot = nslot; b = nb;
+        cur = nxt; fa = fn; sg = sgn; item = nitem; bi = nb;
     }
     if (bad) atomicOr(a.status, kStFormat);
-    if (!R16 && pl.use_list) {
-        // the last workgroup to finish re-arms the list for the next call
-        __syncthreads();
-        if (tid == 0 && atomicAdd(pl.items + 1, 1u) == gridDim.x - 1) {
-            pl.items[0] = 0; pl.items[1] = 0; *pl.listed_hint = n_listed;
-        }
-    }
-#ifdef CMPZ_PHASE_CLOCKS
-    if (tid == 0)
-        for (int k = 0; k < 8; ++k)
-            atomicAdd(reinterpret_cast<unsigned long long *>(a.meta + kMetaClocks) + k, (unsigned long long)clk[k]);
-#endif
 }
 
 }  // namespace
 
-// Returns false when the shape does not fit the fused kernel (caller falls back).
-// `items` is scratch of fused_item_words(numel) 32-bit words, zero before the first call.
-// `hint_host` / `hint_dev`: one word of pinned host memory and its device address.  The kernel
-// for the listed items leaves there how many it found; the next call sizes that kernel's grid by
-// it (a small grid is scheduled and gone quickly when, as usual, nothing is listed).  The word
-// is only a hint: whatever the grid, the kernel works through the whole list.
-bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, const volatile uint32_t *hint_host,
-                         uint32_t *hint_dev, Profiler *prof, hipStream_t st)
+// The fused kernel's plan for one tensor.  Returns false when the shape does not fit it (planes
+// larger than one band with rows wider than kColGroups waves): such tensors take the unfused
+// kernels.
+bool plan_decode_fused(TensorD *t, uint32_t sub)
 {
-    const uint32_t ndec = kBandMax / a.sub;
-    const uint64_t cap = (uint64_t)(ndec - 1) * a.sub + 1;     // a band then spans at most ndec sub-blocks
-    FusedPlan pl;
-    pl.divW = FastDiv::make(a.W);
-    pl.items = items;
-    pl.listed_hint = hint_dev;
-    if (a.HW <= cap) {
-        pl.big = 0; pl.G = (uint32_t)(cap / a.HW); pl.Rb = 0;
-        pl.nitems = (a.planes + pl.G - 1) / pl.G;
-    } else if (a.W <= (uint32_t)(kColGroups * kWave) && a.W <= cap) {
-        pl.big = 1; pl.G = 1; pl.Rb = (uint32_t)(cap / a.W);
-        pl.nitems = a.planes;
+    const uint32_t H = t->shape[2], W = t->shape[3], HW = H * W, planes = t->shape[0] * t->shape[1];
+    const uint32_t ndec = kBandMax / sub;
+    const uint64_t cap = (uint64_t)(ndec - 1) * sub + 1;       // a band then spans at most ndec sub-blocks
+    t->divW = FastDiv::make(W);
+    t->nwg = 0;
+    if (t->numel == 0) return false;
+    if (HW <= cap) {
+        t->big = 0; t->G = (uint32_t)(cap / HW); t->Rb = 0;
+        t->nitems = (planes + t->G - 1) / t->G;
+    } else if (W <= (uint32_t)(kColGroups * kWave) && W <= cap) {
+        t->big = 1; t->G = 1; t->Rb = (uint32_t)(cap / W);
+        t->nitems = planes;
     } else {
         return false;
-    }
-    // every workgroup builds the decode tables once and then loops: no more workgroups than fit the chip
-    const uint32_t want = (pl.nitems + kWaves - 1) / kWaves;
-    const uint32_t grid4 = want < 256u * 4u ? want : 256u * 4u;
-    const uint32_t grid3 = want < 256u * 3u ? want : 256u * 3u;
-    const uint32_t rest_max = (*hint_host == 0) ? 32u : 256u;
-    const uint32_t grid1 = want < rest_max ? want : rest_max;
-    switch (a.sub) {
-    case 32:
-        pl.use_list = 1;
-        launch(prof, kKDecodeFused, k_decode_fused<32, true>, dim3(grid4), dim3(kThreads), st, a, pl);
-        launch(prof, kKDecodeFusedRest, k_decode_fused<32, false>, dim3(grid1), dim3(kThreads), st, a, pl);
-        break;
-    case 64:
-        pl.use_list = 1;
-        launch(prof, kKDecodeFused, k_decode_fused<64, true>, dim3(grid4), dim3(kThreads), st, a, pl);
-        launch(prof, kKDecodeFusedRest, k_decode_fused<64, false>, dim3(grid1), dim3(kThreads), st, a, pl);
-        break;
-    default:
-        pl.use_list = 0;
-        launch(prof, kKDecodeFused, k_decode_fused<128, false>, dim3(grid3), dim3(kThreads), st, a, pl);
-        break;
     }
     return true;
 }
 
-// Words of scratch the item list of a tensor of `numel` elements can need: an item is a whole
-// plane of more than 1921 elements or a group of planes with more than 960 elements together.
-uint64_t fused_item_words(uint64_t numel) { return kItemList + numel / 900 + 64; }
+// One launch over the tensors of the group that have a plan.  Workgroups are dealt to the tensors
+// in proportion to their elements: about eight per CU in total, so that the chip's four resident
+// ones per CU are replaced as they finish and tensors of different cost per element even out;
+// no more than a tensor has items for, at least one.
+void launch_decode_fused(BatchD &b, Profiler *prof, hipStream_t st)
+{
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < b.n; ++k) if (b.t[k].nitems) total += b.t[k].numel;
+    uint32_t grid = 0;
+    for (uint32_t k = 0; k < b.n; ++k) {
+        TensorD &t = b.t[k];
+        t.wg_base = grid;
+        t.nwg = 0;
+        if (!t.nitems) continue;
+        const uint64_t share = ((uint64_t)t.numel * 2048 + total - 1) / total;
+        const uint64_t most = (t.nitems + kWaves - 1) / kWaves;
+        t.nwg = (uint32_t)(share < most ? share : most);
+        if (t.nwg < 1) t.nwg = 1;
+        grid += t.nwg;
+    }
+    if (!grid) return;
+    switch (b.sub) {
+    case 32:  launch(prof, kKDecodeFused, k_decode_fused<32>, dim3(grid), dim3(kThreads), st, b); break;
+    case 64:  launch(prof, kKDecodeFused, k_decode_fused<64>, dim3(grid), dim3(kThreads), st, b); break;
+    default:  launch(prof, kKDecodeFused, k_decode_fused<128>, dim3(grid), dim3(kThreads), st, b); break;
+    }
+}
 
 }  // namespace cmpz

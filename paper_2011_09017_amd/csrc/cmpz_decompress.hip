@@ -287,15 +287,14 @@ __global__ __launch_bounds__(kThreads) void k_col_scan_dequant(DecompressArgs a)
 
 size_t decode_tables_bytes() { return sizeof(DecodeTables); }
 
-void launch_decompress(const DecompressArgs &a, void *tables, uint32_t *items, const volatile uint32_t *hint_host,
-                       uint32_t *hint_dev, Profiler *prof, hipStream_t st)
+// Shapes the fused kernel does not take, and empty tensors (validation only): residuals staged in
+// the output buffer.
+void launch_decompress_unfused(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st)
 {
-    if (a.numel != 0 && launch_decode_fused(a, items, hint_host, hint_dev, prof, st)) return;
     DecodeTables *tb = static_cast<DecodeTables *>(tables);
     launch(prof, kKDecodeTables, k_decode_tables, dim3(1), dim3(1024), st, a, tb);
     if (a.numel == 0) return;
     const DecodeTables *ctb = tb;
-    // shapes the fused kernel does not take: residuals staged in the output buffer
     const uint64_t nsubs = (uint64_t)a.lay.nchunks * a.lay.nsub;
     const uint32_t blocks = (uint32_t)((nsubs + kDecThreads - 1) / kDecThreads);
     switch (a.sub) {

@@ -162,6 +162,42 @@ struct DecompressArgs {
     uint32_t *status;
 };
 
+// ---- decompression: one call handles a batch of containers ----
+struct TensorD {
+    const uint8_t *buf;
+    uint64_t       size;
+    float         *xout;
+    uint32_t       shape[4];
+    uint32_t       numel, eb_bits;
+    float          s;
+    // plan of the fused kernel (nitems == 0: the tensor takes the unfused kernels)
+    uint32_t       wg_base, nwg;            // its workgroups in the launch
+    uint32_t       big, G, Rb, nitems;
+    FastDiv        divW;
+};
+
+struct BatchD {
+    uint32_t  n;
+    uint32_t  radius, sub, guard_shift;
+    uint32_t *meta;
+    uint32_t *status;
+    TensorD   t[kBatchMax];
+};
+
+__host__ __device__ inline DecompressArgs decompress_args(const BatchD &b, const TensorD &t)
+{
+    DecompressArgs a;
+    a.buf = t.buf; a.size = t.size; a.xout = t.xout;
+    a.numel = t.numel; a.planes = t.shape[0] * t.shape[1];
+    a.H = t.shape[2]; a.W = t.shape[3]; a.HW = a.H * a.W;
+    for (int i = 0; i < 4; ++i) a.shape[i] = t.shape[i];
+    a.radius = b.radius; a.sub = b.sub; a.guard_shift = b.guard_shift; a.eb_bits = t.eb_bits;
+    a.s = t.s;
+    a.lay = make_layout(t.numel, b.radius, b.sub);
+    a.meta = b.meta; a.status = b.status;
+    return a;
+}
+
 constexpr uint32_t kLB = 11;                      // bits resolved by the first decode table
 struct DecodeTables;                              // cmpz_decode_core.h
 
@@ -257,7 +293,7 @@ __device__ __forceinline__ uint32_t rank_within_length(uint32_t L, uint32_t (*wa
 // Kernel identifiers for the optional per-kernel timing (cmp_profile).
 enum KernelId : int {
     kKQuantLorenzoHist = 0, kKCodebook, kKLengths, kKScan, kKPack, kKClear,
-    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKDecodeFusedRest, kKControllerStats,
+    kKDecodeTables, kKDecode, kKPatchOutliers, kKRowScan, kKColScanDequant, kKDecodeFused, kKControllerStats,
     kKernelCount
 };
 extern const char *const kKernelNames[kKernelCount];
@@ -299,11 +335,9 @@ void launch_codebook(const BatchC &b, Profiler *prof, hipStream_t st);
 void launch_pack(const BatchC &b, Profiler *prof, hipStream_t st);
 void launch_clear(const BatchC &b, Profiler *prof, hipStream_t st);
 size_t decode_tables_bytes();
-void launch_decompress(const DecompressArgs &a, void *tables, uint32_t *items, const volatile uint32_t *hint_host,
-                       uint32_t *hint_dev, Profiler *prof, hipStream_t st);
-bool launch_decode_fused(const DecompressArgs &a, uint32_t *items, const volatile uint32_t *hint_host,
-                         uint32_t *hint_dev, Profiler *prof, hipStream_t st);
-uint64_t fused_item_words(uint64_t numel);
+bool plan_decode_fused(TensorD *t, uint32_t sub);
+void launch_decode_fused(BatchD &b, Profiler *prof, hipStream_t st);
+void launch_decompress_unfused(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st);
 
 // Error-bound estimator: device scratch (zero between calls) and result record.
 constexpr uint32_t kMaxBatch = 65536;

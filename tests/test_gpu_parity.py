@@ -427,6 +427,19 @@ def test_batch_equals_single_calls_equals_oracle(gpu, orc):
             assert single.last_status() == 0
             orc_rc, oy = orc.decompress(obuf, x.shape, eb, ocfg)
             assert np.array_equal(y.cpu().numpy().view(np.uint32), oy.view(np.uint32))
+        # all containers decoded by one call: the same bits as the single calls and the oracle
+        ys = ctx.decompress_batch(outs, sizes, [x.shape for x in xs], ebs)
+        assert ctx.last_status() == 0
+        for x, eb, out, size, y in zip(xs, ebs, outs, sizes, ys):
+            y1 = single.decompress(out, size, x.shape, eb)
+            assert torch.equal(y.view(torch.int32), y1.view(torch.int32))
+    # a damaged container among them is reported, the others still come out
+    dam = [o.clone() for o in outs]
+    dam[3][0] ^= 1
+    ys2 = ctx.decompress_batch(dam, sizes, [x.shape for x in xs], ebs)
+    assert ctx.last_status() == gpu.CMP_E_FORMAT
+    for k in (0, 4, 8, 28):
+        assert torch.equal(ys2[k].view(torch.int32), ys[k].view(torch.int32))
     # a context smaller than the batch works it off in several groups
     small = make_ctx(gpu, sub=sub, max_numel=max(x.numel() for x in xs))
     outs2, sizes2, rc = small.compress_batch(xs, ebs)
