@@ -122,6 +122,24 @@ int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float e
 int cmp_compress_batch(cmp_ctx *ctx, int n, const float *const *d_x, const int64_t (*shapes)[4], const float *eb,
                        void *const *d_out, const size_t *out_cap, size_t *h_sizes, void *stream);
 
+/* cmp_compress for callers that cannot allocate device memory and therefore cannot hold a
+ * context: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * It runs the same kernels as cmp_compress and gives the same container, with its scratch in an
+ * array that is part of the library's device image: about 11.7 MB on every GPU the library is
+ * loaded on, held until the process ends.  The call allocates nothing (no hipMalloc, no
+ * hipFree, no pinned memory) and does not synchronise.
+ *   device   the GPU of d_x and d_out;
+ *   cfg      NULL = defaults; max_numel is ignored;
+ *   limit    at most CMP_STATIC_MAX_NUMEL elements: larger tensors are refused with CMP_E_ARG.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race; issue them on one stream, or order them with events.  Conditions only the GPU
+ * sees are recorded in the container header and reported by cmp_compressed_size (whose ctx may
+ * be NULL: the current device is used).  Capacity below the container's fixed sections:
+ * CMP_E_NOSPACE. */
+#define CMP_STATIC_MAX_NUMEL (1u << 22)
+int cmp_compress_static(int device, const cmp_config *cfg, const float *d_x, const int64_t shape[4], float eb,
+                        void *d_out, size_t out_cap, void *stream);
+
 /* cmp_compress in two calls, for callers that pipeline tensors over several streams: the single
  * workgroup that builds the Huffman codebook leaves the GPU idle, and with begin(i+1) issued on
  * one stream while finish(i) runs on another the first sweep of the next tensor fills that time.
@@ -139,7 +157,7 @@ int cmp_compress_finish(cmp_ctx *ctx, void *d_out, size_t out_cap, size_t *h_siz
 
 /* Waits for `stream`, reads the header of a container produced by cmp_compress
  * and stores its size in bytes (the compression-ratio monitor of Section 4.4
- * reads this).  Returns CMP_E_NOSPACE (h_size = bytes needed) if that compress
+ * reads this; ctx may be NULL, the current device is then used).  Returns CMP_E_NOSPACE (h_size = bytes needed) if that compress
  * ran out of room, CMP_W_RANGE if it clamped values, CMP_E_FORMAT if d_buf does
  * not start with a container header. */
 int cmp_compressed_size(cmp_ctx *ctx, const void *d_buf, size_t *h_size, void *stream);

@@ -23,7 +23,7 @@ CMP_STAGE_OUTLIER_IDX, CMP_STAGE_OUTLIER_VAL = 4, 5
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
            "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",
            "cmp_profile", "cmp_profile_read", "cmp_default_controller_config", "cmp_estimate_eb",
-           "cmp_compress_begin", "cmp_compress_finish", "cmp_compress_batch", "cmp_decompress_batch"]
+           "cmp_compress_begin", "cmp_compress_finish", "cmp_compress_batch", "cmp_decompress_batch", "cmp_compress_static"]
 
 
 class cmp_controller_config(C.Structure):
@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         L.cmp_strerror.argtypes = [i32]; L.cmp_strerror.restype = C.c_char_p
         L.cmp_compress_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]; L.cmp_compress_batch.restype = i32
         L.cmp_decompress_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]; L.cmp_decompress_batch.restype = i32
+        L.cmp_compress_static.argtypes = [i32, vp, vp, vp, C.c_float, vp, sz, vp]; L.cmp_compress_static.restype = i32
         L.cmp_compress_begin.argtypes = [vp, vp, vp, C.c_float, vp]; L.cmp_compress_begin.restype = i32
         L.cmp_compress_finish.argtypes = [vp, vp, sz, vp, vp]; L.cmp_compress_finish.restype = i32
         L.cmp_default_controller_config.argtypes = [vp]; L.cmp_default_controller_config.restype = None
@@ -118,6 +119,16 @@ def cmp_compress_batch(ctx, d_xs, shapes, ebs, d_outs, out_caps, want_sizes: boo
     sizes = (C.c_size_t * n)()
     rc = lib().cmp_compress_batch(ctx, n, xs, sh, eb, outs, caps, sizes if want_sizes else None, stream)
     return rc, ([int(v) for v in sizes] if want_sizes else None)
+
+
+CMP_STATIC_MAX_NUMEL = 1 << 22
+
+
+def cmp_compress_static(device: int, cfg: "cmp_config | None", d_x: int, shape, eb: float, d_out: int, out_cap: int,
+                        stream: int) -> int:
+    s = _shape4(shape)
+    return lib().cmp_compress_static(device, C.addressof(cfg) if cfg is not None else None, d_x, C.addressof(s),
+                                     C.c_float(eb), d_out, out_cap, stream)
 
 
 def cmp_compressed_size(ctx, d_buf: int, stream: int):

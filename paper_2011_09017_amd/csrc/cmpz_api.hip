@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 namespace cmpz {
@@ -355,6 +356,70 @@ int cmp_compress(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float e
                               stream);
 }
 
+// ---- compression without a context and without any allocation ---------------------------------
+// The scratch of this entry point: one array per GPU, in the library's device image, held until
+// the process ends.  Host code never uses the array's name as an address: every device has its
+// own copy at its own address, looked up once (static_scratch_of) and kept.
+constexpr uint64_t kStaticMaxNumel = CMP_STATIC_MAX_NUMEL;
+constexpr uint64_t kStaticBytes    = 2 * (kStaticMaxNumel + (uint64_t)(kBatchMax + 1) * kChunk) + (3ull << 20);
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+uint8_t   *g_static_ptr[kMaxDevices];          // per device: address of its copy of `scratch`
+
+// Device `device` must be current.  Returns NULL when the lookup fails.
+uint8_t *static_scratch_of(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_static_ptr[device] = static_cast<uint8_t *>(p);
+    }
+    return g_static_ptr[device];
+}
+
+}  // namespace
+
+int cmp_compress_static(int device, const cmp_config *cfg, const float *d_x, const int64_t shape[4], float eb,
+                        void *d_out, size_t out_cap, void *stream)
+{
+    cmp_config c;
+    if (cfg) c = *cfg; else cmp_default_config(&c);
+    c.max_numel = kStaticMaxNumel;
+    if (!config_ok(c)) return CMP_E_ARG;
+    if (!d_out || (reinterpret_cast<uintptr_t>(d_out) & 15)) return CMP_E_ARG;
+    CheckedTensor ck;
+    const int rc = check_tensor(c, d_x, shape, eb, &ck);     // refuses more than CMP_STATIC_MAX_NUMEL elements
+    if (rc != CMP_OK) return rc;
+    if (out_cap < ck.lay.off_payload) return CMP_E_NOSPACE;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess) return CMP_E_HIP;
+    if (device < 0 || device >= ndev) return CMP_E_ARG;
+    DeviceGuard guard(device);
+    if (!guard.ok) return CMP_E_HIP;
+    uint8_t *base = static_scratch_of(device);
+    if (!base) return CMP_E_HIP;
+    Scratch sc;
+    if (carve_scratch(&sc, base, kStaticMaxNumel, nullptr) > kStaticBytes) return CMP_E_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    BatchC b;
+    group_begin(&b, c, sc);
+    group_add(&b, ck, d_out, out_cap);
+    group_plan_sweep(&b);
+    // the array keeps the last call's contents, whatever that call was: what the first sweep adds
+    // to must start at zero (a fill kernel, so that the call can be captured into a graph)
+    launch_clear(b, nullptr, st);
+    group_launch_begin(b, nullptr, st);
+    group_launch_finish(b, nullptr, st);
+    if (hipGetLastError() != hipSuccess) return CMP_E_HIP;
+    return CMP_OK;
+}
+
 int cmp_compress_begin(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *stream)
 {
     if (!ctx) return CMP_E_ARG;
@@ -403,8 +468,11 @@ int cmp_compress_finish(cmp_ctx *ctx, void *d_out, size_t out_cap, size_t *h_siz
 
 int cmp_compressed_size(cmp_ctx *ctx, const void *d_buf, size_t *h_size, void *stream)
 {
-    if (!ctx || !d_buf || !h_size) return CMP_E_ARG;
-    DeviceGuard guard(ctx->device);
+    if (!d_buf || !h_size) return CMP_E_ARG;
+    int device = 0;
+    if (ctx) device = ctx->device;
+    else if (hipGetDevice(&device) != hipSuccess) return CMP_E_HIP;
+    DeviceGuard guard(device);
     if (!guard.ok) return CMP_E_HIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Header hd;
