@@ -60,13 +60,29 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
 #pragma unroll
                 for (int j = 0; j < 4; ++j) v[j] = (g + j < numel) ? x[g + j] : 0.0f;
             }
+            // Four values at once: while the largest magnitude of x*r (as a bit pattern: a NaN or an
+            // infinity compares above every finite value) stays within the quantiser's range, the
+            // clamp has nothing to do and no event to count.
+            float tt[4];
+            uint32_t mag = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                tt[j] = v[j] * r;
+                const uint32_t a = __float_as_uint(tt[j]) & 0x7fffffffu;
+                mag = a > mag ? a : mag;
+            }
             int q[4];
+            if (mag <= 0x46800000u) {                                // 16384.0f
 #pragma unroll
-            for (int j = 0; j < 4; ++j) q[j] = quant(v[j], r);
-            if (g >= t0) {
+                for (int j = 0; j < 4; ++j) q[j] = (int)__builtin_rintf(tt[j]);
+            } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) events += (g + j < numel) ? clamps(v[j], r) : 0u;
-            }                                                        // (g and t0 are multiples of 4: no straddling)
+                for (int j = 0; j < 4; ++j) q[j] = quant(v[j], r);
+                if (g >= t0) {                                       // (g and t0 are multiples of 4: no straddling)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) events += (g + j < numel) ? clamps(v[j], r) : 0u;
+                }
+            }
             uint2 pk;
             pk.x = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
             pk.y = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
@@ -116,18 +132,42 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
             for (int k = 0; k < 17; ++k) up[k] = Q[li - (int)W - 1 + k];
 
             const uint32_t nval = (t1 - g0 >= 16u) ? 16u : t1 - g0;
+            if (nval == 16u) {
+                // all 16 elements exist: symbols first, the in-range test on the largest of them
+                uint32_t top = 0;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const int keepw = ~__builtin_amdgcn_sbfe((int)mw, k, 1);     // 0 where the row starts
-                const int keeph = ~__builtin_amdgcn_sbfe((int)mh, k, 1);     // 0 in the first row
-                const int d = (cur[k + 1] - (cur[k] & keepw)) - ((up[k + 1] - (up[k] & keepw)) & keeph);
-                const uint32_t sy = (uint32_t)(d + R);
-                const bool in = (sy - 1u) < (uint32_t)(2 * R - 1);           // 1 <= d+R <= 2R-1
-                s[k] = in ? sy : 0u;
-                if ((uint32_t)k < nval) {
-                    nout += in ? 0u : 1u;
+                for (int k = 0; k < 16; ++k) {
+                    const int keepw = ~__builtin_amdgcn_sbfe((int)mw, k, 1);     // 0 where the row starts
+                    const int keeph = ~__builtin_amdgcn_sbfe((int)mh, k, 1);     // 0 in the first row
+                    const int d = (cur[k + 1] - (cur[k] & keepw)) - ((up[k + 1] - (up[k] & keepw)) & keeph);
+                    s[k] = (uint32_t)(d + R);
+                    const uint32_t v1 = s[k] - 1u;                               // in range: 0 <= v1 < 2R-1
+                    top = v1 > top ? v1 : top;
+                }
+                if (top >= (uint32_t)(2 * R - 1)) {                              // rare: some residual is an outlier
+#pragma unroll
+                    for (int k = 0; k < 16; ++k)
+                        if (s[k] - 1u >= (uint32_t)(2 * R - 1)) { s[k] = 0u; ++nout; }
+                }
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
                     if (s[k] == (uint32_t)R) ++zero_run;
                     else atomicAdd(&hist[s[k]], 1u);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const int keepw = ~__builtin_amdgcn_sbfe((int)mw, k, 1);
+                    const int keeph = ~__builtin_amdgcn_sbfe((int)mh, k, 1);
+                    const int d = (cur[k + 1] - (cur[k] & keepw)) - ((up[k + 1] - (up[k] & keepw)) & keeph);
+                    const uint32_t sy = (uint32_t)(d + R);
+                    const bool in = (sy - 1u) < (uint32_t)(2 * R - 1);           // 1 <= d+R <= 2R-1
+                    s[k] = in ? sy : 0u;
+                    if ((uint32_t)k < nval) {
+                        nout += in ? 0u : 1u;
+                        if (s[k] == (uint32_t)R) ++zero_run;
+                        else atomicAdd(&hist[s[k]], 1u);
+                    }
                 }
             }
             if (nval == 16u) {
