@@ -187,7 +187,7 @@ int cmp_last_status(cmp_ctx *ctx, void *stream);
 /* Intermediate results of the LAST cmp_compress on this context, for parity
  * checks.  Stores a device pointer into the context's scratch (valid until the
  * next call on the context) and its size in bytes.  The caller synchronises. */
-#define CMP_STAGE_QUANT_CODES 0   /* uint16[numel]: symbol per element, 0 = outlier            */
+#define CMP_STAGE_QUANT_CODES 0   /* uint16[numel]: symbol per element, 0 = outlier (waits for the GPU) */
 #define CMP_STAGE_HIST        1   /* uint32[2*radius]: occurrences of each symbol              */
 #define CMP_STAGE_LENS        2   /* uint8[2*radius]: Huffman code length, 0 = unused          */
 #define CMP_STAGE_CODES       3   /* uint64[2*radius]: length << 56 | canonical code           */

@@ -22,7 +22,7 @@ using namespace cmpz;
 struct Scratch {
     // compression (see BatchC)
     uint16_t   *sym;
-    uint32_t   *hist, *hist_copy, *enc32, *outl_cnt, *chunk_bits, *range_units, *range_outl, *range_bits, *status;
+    uint32_t   *hist, *hist_copy, *enc32, *outl_cnt, *wide, *chunk_bits, *range_units, *range_outl, *range_bits, *status;
     uint8_t    *lens;
     uint64_t   *codes;
     TensorMeta *tmeta;
@@ -107,6 +107,7 @@ uint64_t carve_scratch(Scratch *sc, uint8_t *base, uint64_t max_numel, uint64_t 
     s.codes = reinterpret_cast<uint64_t *>(carve(8ull * kMaxSym * kBatchMax));
     s.enc32 = reinterpret_cast<uint32_t *>(carve(4ull * kMaxSym * kBatchMax));
     s.outl_cnt = reinterpret_cast<uint32_t *>(carve(4 * s.max_chunks));
+    s.wide = reinterpret_cast<uint32_t *>(carve(16 * s.max_chunks));
     s.chunk_bits = reinterpret_cast<uint32_t *>(carve(4 * s.max_chunks));
     s.range_units = reinterpret_cast<uint32_t *>(carve(4 * s.max_ranges));
     s.range_outl = reinterpret_cast<uint32_t *>(carve(4 * s.max_ranges));
@@ -245,7 +246,8 @@ void group_begin(BatchC *b, const cmp_config &cfg, const Scratch &s)
     std::memset(b, 0, sizeof(*b));
     b->radius = cfg.radius; b->sub = cfg.sub; b->guard_shift = cfg.guard_shift;
     b->sym = s.sym; b->hist = s.hist; b->hist_copy = s.hist_copy; b->lens = s.lens; b->codes = s.codes;
-    b->enc32 = s.enc32; b->outl_cnt = s.outl_cnt; b->chunk_bits = s.chunk_bits;
+    b->enc32 = s.enc32; b->outl_cnt = s.outl_cnt; b->wide = s.wide; b->chunk_bits = s.chunk_bits;
+    b->sym_off = cfg.radius > 128 ? cfg.radius - 128 : 0;
     b->range_units = s.range_units; b->range_outl = s.range_outl; b->range_bits = s.range_bits;
     b->tmeta = s.tmeta; b->status = s.status;
 }
@@ -559,7 +561,16 @@ int cmp_debug_stage(cmp_ctx *ctx, int which, const void **d_ptr, size_t *bytes)
     if (!ctx || !d_ptr || !bytes) return CMP_E_ARG;
     const size_t nsym = 2 * (size_t)ctx->cfg.radius;
     switch (which) {
-    case CMP_STAGE_QUANT_CODES: *d_ptr = ctx->s.sym; *bytes = 2 * (size_t)ctx->last_numel; return CMP_OK;
+    case CMP_STAGE_QUANT_CODES: {
+        // quarter chunks kept with 8 bits per symbol are rewritten with 16 first (waits for the GPU)
+        DeviceGuard guard(ctx->device);
+        if (!guard.ok) return CMP_E_HIP;
+        if (hipDeviceSynchronize() != hipSuccess) return CMP_E_HIP;
+        launch_widen(ctx->s.sym, ctx->s.wide, ctx->cfg.radius > 128 ? ctx->cfg.radius - 128 : 0,
+                     (uint32_t)((ctx->last_numel + kChunk - 1) / kChunk), nullptr);
+        if (hipDeviceSynchronize() != hipSuccess) return CMP_E_HIP;
+        *d_ptr = ctx->s.sym; *bytes = 2 * (size_t)ctx->last_numel; return CMP_OK;
+    }
     case CMP_STAGE_HIST: *d_ptr = ctx->s.hist_copy; *bytes = 4 * nsym; return CMP_OK;
     case CMP_STAGE_LENS: *d_ptr = ctx->s.lens; *bytes = nsym; return CMP_OK;
     case CMP_STAGE_CODES: *d_ptr = ctx->s.codes; *bytes = 8 * nsym; return CMP_OK;

@@ -112,7 +112,10 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist(BatchC b,
     }
     if (tid < kTileChunks) {
         const uint64_t c = (uint64_t)blockIdx.x * kTileChunks + tid;
-        if (c < tc.nchunks) b.outl_cnt[tc.chunk_base + c] = ocnt[tid];
+        if (c < tc.nchunks) {
+            b.outl_cnt[tc.chunk_base + c] = ocnt[tid];
+            for (int k = 0; k < 4; ++k) b.wide[(tc.chunk_base + c) * 4 + k] = 1;      // always 16-bit symbols
+        }
     }
     // range events: one atomic per wave
     for (int o = 32; o > 0; o >>= 1) events += __shfl_down(events, o);

@@ -133,7 +133,11 @@ struct BatchC {
     uint32_t sweep_chunks;      // chunks per workgroup in the first sweep
     uint32_t sweep_wgs, pack_wgs, total_chunks;
     // context scratch
-    uint16_t   *sym;            // whole chunks
+    uint16_t   *sym;            // whole chunks of 4096 symbols, 8192 bytes apart.  Every quarter of a chunk (1024
+                                // symbols, 2048 bytes apart) holds 16 bits per symbol or, if not marked wide,
+                                // 8 bits (symbol - sym_off) in its first 1024 bytes
+    uint32_t   *wide;           // [global chunk][quarter]: nonzero = 16-bit symbols
+    uint32_t    sym_off;        // radius - 128 (0 for radii up to 128): byte b stands for symbol b + sym_off
     uint32_t   *hist;           // [slot][kHistCopies][kMaxSym], zero between calls
     uint32_t   *hist_copy;      // [slot][kMaxSym]
     uint8_t    *lens;           // [slot][kMaxSym]
@@ -334,6 +338,7 @@ bool sweep1_tiled_fits(uint32_t W);
 void launch_codebook(const BatchC &b, Profiler *prof, hipStream_t st);
 void launch_pack(const BatchC &b, Profiler *prof, hipStream_t st);
 void launch_clear(const BatchC &b, Profiler *prof, hipStream_t st);
+void launch_widen(uint16_t *sym, uint32_t *wide, uint32_t sym_off, uint32_t nchunks, hipStream_t st);
 size_t decode_tables_bytes();
 bool plan_decode_fused(TensorD *t, uint32_t sub);
 void launch_decode_fused(BatchD &b, Profiler *prof, hipStream_t st);

@@ -50,9 +50,9 @@ __device__ __forceinline__ void unpack8(const uint4 &v, uint32_t s[8])
 }
 
 // ---------------------------------------------------------------------------
-// Bit counts.  A wave takes whole chunks; per step every lane holds 8 consecutive symbols
-// (one 128-bit load, consecutive lanes consecutive addresses), so a sub-block of 32, 64 or 128
-// codes is 4, 8 or 16 neighbouring lanes of one DPP row.
+// Bit counts.  A wave takes whole chunks; per step every lane holds 8 consecutive 16-bit symbols
+// or 16 consecutive bytes (one 128-bit load, consecutive lanes consecutive addresses), so a
+// sub-block of 32, 64 or 128 codes is a few neighbouring lanes of one DPP row.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
 {
@@ -73,37 +73,71 @@ __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
     const uint16_t *__restrict__ sym = b.sym + (uint64_t)tc.chunk_base * kChunk;
     const Layout lay = make_layout(numel, b.radius, b.sub);
     uint16_t *__restrict__ sub_bits = reinterpret_cast<uint16_t *>(tc.out + lay.off_sub_bits);
-    const uint32_t group = b.sub / 8;                // lanes per sub-block: 4, 8 or 16
 
     for (uint32_t q = wv; q < nq; q += kWaves) {
         const uint32_t c = c0 + q;
         const uint32_t e0 = c * kChunk;              // first element of the chunk
         const bool full = numel - e0 >= kChunk;
-        uint4 v[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j)                  // the symbol scratch holds whole chunks: always in bounds
-            v[j] = *reinterpret_cast<const uint4 *>(sym + e0 + (uint32_t)(j * kWave + lane) * 8u);
         uint32_t chunk_bits = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint32_t s[8];
-            unpack8(v[j], s);
-            if (!full) {
-                const uint32_t i0 = e0 + (uint32_t)(j * kWave + lane) * 8u;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) if (i0 + k >= numel) s[k] = kPastEnd;
-            }
-            uint32_t bits = 0;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) bits += L[s[k]];
+        // sub-block bit counts from the lanes' bit counts
+        auto emit = [&](uint32_t bits, uint32_t first_sub, uint32_t group) {
             const uint32_t inc = wave_inclusive_sum(bits);
             const uint32_t exc = inc - bits;
             // the first lane of a sub-block sits group-1 lanes below its last lane, in the same DPP row
-            const uint32_t first_exc = (group == 16) ? dpp_u32<0x11F, 0xf>(exc)
-                                     : (group == 8)  ? dpp_u32<0x117, 0xf>(exc) : dpp_u32<0x113, 0xf>(exc);
+            const uint32_t first_exc = (group == 16) ? dpp_u32<0x11F, 0xf>(exc) : (group == 8) ? dpp_u32<0x117, 0xf>(exc)
+                                     : (group == 4)  ? dpp_u32<0x113, 0xf>(exc) : dpp_u32<0x111, 0xf>(exc);
             if (((uint32_t)lane & (group - 1)) == group - 1)
-                sub_bits[(uint64_t)c * lay.nsub + (uint32_t)(j * kWave + lane) / group] = (uint16_t)(inc - first_exc);
+                sub_bits[(uint64_t)c * lay.nsub + first_sub + (uint32_t)lane / group] = (uint16_t)(inc - first_exc);
             chunk_bits += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+        };
+        // the four quarters of the chunk, each with 16-bit symbols (8 per lane and step, two steps, a
+        // sub-block is 4, 8 or 16 lanes) or with bytes (16 per lane, one step, a sub-block is 2, 4 or 8
+        // lanes); all loads first (the scratch holds whole chunks: always in bounds)
+        const uint4 wq = *reinterpret_cast<const uint4 *>(b.wide + (uint64_t)(tc.chunk_base + c) * 4);
+        const bool wide[4] = {__builtin_amdgcn_readfirstlane(wq.x) != 0, __builtin_amdgcn_readfirstlane(wq.y) != 0,
+                              __builtin_amdgcn_readfirstlane(wq.z) != 0, __builtin_amdgcn_readfirstlane(wq.w) != 0};
+        uint4 v[4][2];
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) {
+            const uint16_t *slot = sym + e0 + 1024u * qt;
+            if (wide[qt]) {
+                v[qt][0] = *reinterpret_cast<const uint4 *>(slot + (uint32_t)lane * 8u);
+                v[qt][1] = *reinterpret_cast<const uint4 *>(slot + 512u + (uint32_t)lane * 8u);
+            } else {
+                v[qt][0] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(slot) + (uint32_t)lane * 16u);
+                v[qt][1] = v[qt][0];
+            }
+        }
+        const uint8_t *Lo = L + b.sym_off;
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) {
+            if (wide[qt]) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    uint32_t s[8];
+                    unpack8(v[qt][j], s);
+                    if (!full) {
+                        const uint32_t i0 = e0 + 1024u * qt + 512u * j + (uint32_t)lane * 8u;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) if (i0 + k >= numel) s[k] = kPastEnd;
+                    }
+                    uint32_t bits = 0;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) bits += L[s[k]];
+                    emit(bits, (1024u * qt + 512u * j) / b.sub, b.sub / 8);
+                }
+            } else {
+                const uint32_t w[4] = {v[qt][0].x, v[qt][0].y, v[qt][0].z, v[qt][0].w};
+                const uint32_t i0 = e0 + 1024u * qt + (uint32_t)lane * 16u;
+                uint32_t bits = 0;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const uint32_t byte = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
+                    const uint32_t len = Lo[byte];
+                    bits += (full || i0 + k < numel) ? len : 0u;
+                }
+                emit(bits, (1024u * qt) / b.sub, b.sub / 16);
+            }
         }
         if (lane == 0) { bits_s[q] = chunk_bits; b.chunk_bits[tc.chunk_base + c] = chunk_bits; }
     }
@@ -378,18 +412,36 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
             ubase = done;
         };
 
+        // per quarter of the chunk: 16-bit symbols, else bytes (uniform)
+        const uint4 wq = *reinterpret_cast<const uint4 *>(b.wide + (uint64_t)(tc.chunk_base + c) * 4);
+        const uint32_t wide_mask = (__builtin_amdgcn_readfirstlane(wq.x) ? 1u : 0u) | (__builtin_amdgcn_readfirstlane(wq.y) ? 2u : 0u) |
+                                   (__builtin_amdgcn_readfirstlane(wq.z) ? 4u : 0u) | (__builtin_amdgcn_readfirstlane(wq.w) ? 8u : 0u);
+        const uint8_t *__restrict__ sb = reinterpret_cast<const uint8_t *>(sym + e0);
+        auto unpack_bytes = [&](uint32_t w, uint32_t *s4) {
+            s4[0] = (w & 0xffu) + b.sym_off; s4[1] = ((w >> 8) & 0xffu) + b.sym_off;
+            s4[2] = ((w >> 16) & 0xffu) + b.sym_off; s4[3] = (w >> 24) + b.sym_off;
+        };
         if (short_codes) {
-            // 16 symbols per lane and step, the next step's symbols in flight
-            uint4 lo = *reinterpret_cast<const uint4 *>(sym + e0 + (uint32_t)lane * 16u);
-            uint4 hi = *reinterpret_cast<const uint4 *>(sym + e0 + (uint32_t)lane * 16u + 8u);
+            // 16 symbols per lane and step, the next step's symbols in flight.  A step is a quarter of the
+            // chunk (2048 bytes apart): a lane's 16 symbols are 32 bytes of a wide quarter, 16 of a narrow
+            // one (the second load then repeats the first)
+            auto fetch = [&](uint32_t qt, uint4 &a, uint4 &c2) {
+                const bool wd = (wide_mask >> qt) & 1u;
+                const uint8_t *p = sb + 2048u * qt + (((uint32_t)lane * 16u) << (wd ? 1 : 0));
+                a = *reinterpret_cast<const uint4 *>(p);
+                c2 = *reinterpret_cast<const uint4 *>(p + (wd ? 16u : 0u));
+            };
+            uint4 lo, hi;
+            fetch(0, lo, hi);
 #pragma unroll 1
             for (uint32_t it = 0; it < 4; ++it) {
                 const uint32_t i0 = e0 + it * 1024u + (uint32_t)lane * 16u;
-                const uint32_t nx = (it < 3) ? i0 + 1024u : i0;       // the last step fetches its own symbols again
-                const uint4 nlo = *reinterpret_cast<const uint4 *>(sym + nx);
-                const uint4 nhi = *reinterpret_cast<const uint4 *>(sym + nx + 8u);
+                const bool wide = (wide_mask >> it) & 1u;
+                uint4 nlo, nhi;
+                fetch(it < 3 ? it + 1 : it, nlo, nhi);                    // the last step fetches its own symbols again
                 uint32_t s[16];
-                unpack8(lo, s); unpack8(hi, s + 8);
+                if (wide) { unpack8(lo, s); unpack8(hi, s + 8); }
+                else { unpack_bytes(lo.x, s); unpack_bytes(lo.y, s + 4); unpack_bytes(lo.z, s + 8); unpack_bytes(lo.w, s + 12); }
                 if (!full) {
 #pragma unroll
                     for (int k = 0; k < 16; ++k) if (i0 + k >= numel) s[k] = kPastEnd;
@@ -401,9 +453,15 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
 #pragma unroll 1
             for (uint32_t it = 0; it < 8; ++it) {
                 const uint32_t i0 = e0 + it * 512u + (uint32_t)lane * 8u;
-                const uint4 v = *reinterpret_cast<const uint4 *>(sym + i0);
                 uint32_t s[8];
-                unpack8(v, s);
+                if ((wide_mask >> (it >> 1)) & 1u) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(sym + i0);
+                    unpack8(v, s);
+                } else {
+                    // quarter it/2, its first or second 512 bytes
+                    const uint2 v = *reinterpret_cast<const uint2 *>(sb + 2048u * (it >> 1) + 512u * (it & 1u) + (uint32_t)lane * 8u);
+                    unpack_bytes(v.x, s); unpack_bytes(v.y, s + 4);
+                }
                 if (!full) {
 #pragma unroll
                     for (int k = 0; k < 8; ++k) if (i0 + k >= numel) s[k] = kPastEnd;
@@ -426,7 +484,35 @@ __global__ __launch_bounds__(kThreads) void k_clear(BatchC b)
     if (threadIdx.x == 0) b.tmeta[ti].range_events = 0;
 }
 
+// Quarter chunks stored with 8 bits per symbol, rewritten in place with 16 (for inspection of the
+// symbols).  One workgroup of 64 threads per quarter.
+__global__ __launch_bounds__(64) void k_widen(uint16_t *sym, uint32_t *wide, uint32_t sym_off)
+{
+    const uint32_t qd = blockIdx.x, lane = threadIdx.x;
+    if (wide[qd]) return;                            // uniform
+    uint16_t *slot = sym + (uint64_t)qd * 1024u;
+    const uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(slot) + 16u * lane);
+    __syncthreads();                                 // every byte is read before the slot is overwritten
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const uint32_t a = ((w[k >> 1] >> (16 * (k & 1))) & 0xffu) + sym_off;
+        const uint32_t b2 = ((w[k >> 1] >> (16 * (k & 1) + 8)) & 0xffu) + sym_off;
+        o[k] = a | (b2 << 16);
+    }
+    *reinterpret_cast<uint4 *>(slot + 16u * lane) = make_uint4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<uint4 *>(slot + 16u * lane + 8u) = make_uint4(o[4], o[5], o[6], o[7]);
+    __syncthreads();
+    if (lane == 0) wide[qd] = 1;
+}
+
 }  // namespace
+
+void launch_widen(uint16_t *sym, uint32_t *wide, uint32_t sym_off, uint32_t nchunks, hipStream_t st)
+{
+    if (nchunks) hipLaunchKernelGGL(k_widen, dim3(4 * nchunks), dim3(64), 0, st, sym, wide, sym_off);
+}
 
 void launch_clear(const BatchC &b, Profiler *prof, hipStream_t st)
 {

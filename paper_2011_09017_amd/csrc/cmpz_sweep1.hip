@@ -7,9 +7,12 @@
 // elements.  Phase A quantises the chunk and the W+1 elements before it once
 // each, with 128-bit loads, into an LDS array of int16 (|q| <= 16384).  Phase B
 // gives every thread 16 consecutive elements: residuals from the LDS values,
-// symbols, histogram (LDS-private, the zero residual counted per wave), two
-// 128-bit symbol stores.  Rows wider than the halo capacity take the untiled
-// kernel in cmpz_compress.hip.
+// symbols, histogram (LDS-private, the zero residual counted per wave).  A wave's
+// 1024 symbols (a quarter of the chunk) are stored with 8 bits each if they all
+// lie within 127 of the zero residual (the usual case), one 128-bit store per
+// thread, otherwise with 16 bits, two stores: the second sweep reads that scratch
+// twice.  Rows wider than the halo capacity take the untiled kernel in
+// cmpz_compress.hip.
 #include "cmpz_internal.h"
 
 namespace cmpz {
@@ -96,6 +99,7 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
         const uint32_t g0 = t0 + i0;
         uint32_t s[16];
         uint32_t nout = 0;
+        uint32_t bytes_or = 0;                                       // OR of symbol - sym_off over the thread's elements
         if (g0 < t1) {
             // plane coordinates of the first element, then bit masks over the 16 elements:
             // mw bit j = element j starts a row, mh bit j = element j lies in row 0 of its plane
@@ -143,11 +147,13 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
                     s[k] = (uint32_t)(d + R);
                     const uint32_t v1 = s[k] - 1u;                               // in range: 0 <= v1 < 2R-1
                     top = v1 > top ? v1 : top;
+                    bytes_or |= s[k] - b.sym_off;
                 }
                 if (top >= (uint32_t)(2 * R - 1)) {                              // rare: some residual is an outlier
 #pragma unroll
                     for (int k = 0; k < 16; ++k)
                         if (s[k] - 1u >= (uint32_t)(2 * R - 1)) { s[k] = 0u; ++nout; }
+                    bytes_or = 0x100u;                                           // the outlier symbol has no byte form
                 }
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
@@ -164,20 +170,41 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
                     const bool in = (sy - 1u) < (uint32_t)(2 * R - 1);           // 1 <= d+R <= 2R-1
                     s[k] = in ? sy : 0u;
                     if ((uint32_t)k < nval) {
+                        bytes_or |= in ? sy - b.sym_off : 0x100u;
                         nout += in ? 0u : 1u;
                         if (s[k] == (uint32_t)R) ++zero_run;
                         else atomicAdd(&hist[s[k]], 1u);
                     }
                 }
             }
-            if (nval == 16u) {
-                uint4 o0, o1;
-                o0.x = s[0] | (s[1] << 16); o0.y = s[2] | (s[3] << 16); o0.z = s[4] | (s[5] << 16); o0.w = s[6] | (s[7] << 16);
-                o1.x = s[8] | (s[9] << 16); o1.y = s[10] | (s[11] << 16); o1.z = s[12] | (s[13] << 16); o1.w = s[14] | (s[15] << 16);
-                *reinterpret_cast<uint4 *>(sym + g0) = o0;
-                *reinterpret_cast<uint4 *>(sym + g0 + 8) = o1;
-            } else {
-                for (uint32_t k = 0; k < nval; ++k) sym[g0 + k] = (uint16_t)s[k];
+        }
+        {
+            // the wave's quarter of the chunk: bytes if every symbol has a byte form.  The scratch holds
+            // whole chunks: the stores past the end of the tensor stay inside the chunk's slot.
+            const bool wide_q = __ballot(bytes_or > 0xffu) != 0;         // uniform in the wave
+            const uint32_t quarter = (uint32_t)tid >> 6;
+            if (lane == 0) b.wide[(uint64_t)(tc.chunk_base + c) * 4 + quarter] = wide_q ? 1u : 0u;
+            if (g0 < t1) {
+                if (wide_q) {
+                    uint4 o0, o1;
+                    o0.x = s[0] | (s[1] << 16); o0.y = s[2] | (s[3] << 16); o0.z = s[4] | (s[5] << 16); o0.w = s[6] | (s[7] << 16);
+                    o1.x = s[8] | (s[9] << 16); o1.y = s[10] | (s[11] << 16); o1.z = s[12] | (s[13] << 16); o1.w = s[14] | (s[15] << 16);
+                    *reinterpret_cast<uint4 *>(sym + g0) = o0;
+                    *reinterpret_cast<uint4 *>(sym + g0 + 8) = o1;
+                } else {
+                    // (symbols past the end of the tensor may not fit a byte: whatever they leave is never read)
+                    uint32_t o[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const uint32_t b0 = s[4 * k] - b.sym_off, b1 = s[4 * k + 1] - b.sym_off;
+                        const uint32_t b2 = s[4 * k + 2] - b.sym_off, b3 = s[4 * k + 3] - b.sym_off;
+                        o[k] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);       // no masks: only positions past the end
+                                                                                // can exceed a byte, and they spill upward
+                    }
+                    // the quarter's slot starts where its 16-bit symbols would; the wave's bytes fill its first half
+                    *reinterpret_cast<uint4 *>(reinterpret_cast<uint8_t *>(sym + t0 + 1024u * quarter) + 16u * lane) =
+                        make_uint4(o[0], o[1], o[2], o[3]);
+                }
             }
         }
         if (nout) atomicAdd(&ocnt, nout);
