@@ -359,20 +359,26 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
                 }
                 orank += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
             }
-            // bit offsets of the lanes
+            // bit offsets of the lanes; in the short-code case the table entries stay in registers for the packing
             uint32_t bits = 0;
-            if (short_codes) { _Pragma("unroll") for (int k = 0; k < n; ++k) bits += table32[s[k]] & 31u; }
+            uint32_t e[n];
+            if (short_codes) { _Pragma("unroll") for (int k = 0; k < n; ++k) { e[k] = table32[s[k]]; bits += e[k] & 31u; } }
             else             { _Pragma("unroll") for (int k = 0; k < n; ++k) bits += (uint32_t)(table[s[k]] >> 56); }
             const uint32_t inc = wave_inclusive_sum(bits);
             uint32_t pos = bitpos - ubase * 128u + inc - bits;        // bit position in the image
             if (short_codes) {
-                _Pragma("unroll") for (int k = 0; k < n; ++k) {
-                    const uint32_t e = table32[s[k]];
-                    const uint32_t code = e & ~31u, o = pos & 31u;    // left-aligned code
+                // two codewords (at most 54 bits together) go into the image as one: three LDS atomics per pair
+                _Pragma("unroll") for (int k = 0; k < n; k += 2) {
+                    const uint32_t c0 = e[k] & ~31u, l0 = e[k] & 31u;               // left-aligned codes
+                    const uint32_t c1 = e[k + 1] & ~31u, l1 = e[k + 1] & 31u;
+                    const uint64_t second = (((uint64_t)c1) << 32) >> l0;
+                    const uint32_t hi = c0 | (uint32_t)(second >> 32), lo = (uint32_t)second;
+                    const uint32_t o = pos & 31u;
                     uint32_t *w = img + (pos >> 5);
-                    atomicOr(w, code >> o);
-                    atomicOr(w + 1, __builtin_amdgcn_alignbit(code, 0u, o));   // the part that spills over
-                    pos += e & 31u;
+                    atomicOr(w, hi >> o);
+                    atomicOr(w + 1, __builtin_amdgcn_alignbit(hi, lo, o));
+                    atomicOr(w + 2, __builtin_amdgcn_alignbit(lo, 0u, o));           // the part that spills over
+                    pos += l0 + l1;
                 }
             } else {
                 _Pragma("unroll") for (int k = 0; k < n; ++k) {
