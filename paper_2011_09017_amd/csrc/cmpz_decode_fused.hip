@@ -23,9 +23,10 @@
 // straight from memory instead).  In a band without outliers a lane adds up its
 // residuals along the row while it decodes them, so what it stores is already the
 // row prefix sum up to a per-lane carry; one segmented scan over the lanes'
-// totals yields the carries, and the column pass adds them on the fly.  A band
-// with outliers stores plain residuals, patches the outliers in and runs an
-// explicit row scan.
+// totals yields the carries, and the column pass (one lane per column, eight
+// rows in flight) adds them on the fly, de-quantises and stores.  A band with
+// outliers stores plain residuals, patches the outliers in and runs an explicit
+// row scan.
 // Software pipeline: the bit counts of the next band are fetched during the
 // decode of the current one, and its payload during the column pass.
 #include "cmpz_decode_core.h"
@@ -397,82 +398,56 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
             stage_load(sgn, s0, s1);
         }
 
-        // ---- column prefix sums (adding the lanes' carries); wide rows are de-quantised and stored from here ----
-        const bool direct = W >= 32;                     // a wave then stores runs of >= 128 bytes
+        // ---- column prefix sums (adding the lanes' carries), de-quantisation, stores: one lane per column ----
         const uint32_t nrow = pl.big ? rows : H;
         // byte offsets from the band's first output element: the stores then take a uniform base
         // and a 32-bit offset per lane
         char *__restrict__ band_out = reinterpret_cast<char *>(a.xout + e0);
-        auto walk = [&](auto direct_c, uint32_t col, int32_t acc) -> int32_t {
-            constexpr bool kDirect = decltype(direct_c)::value;
+        auto walk = [&](uint32_t col, int32_t acc) -> int32_t {
             const uint32_t p = pl.big ? 0u : pl.divW.div(col);
             const uint32_t w = col - p * W;
             uint32_t u = p * HW + w + u0;
             uint32_t off = (p * HW + w) * 4u;
-            uint32_t h = 0;
-            for (; h + kRows <= nrow; h += kRows) {      // kRows rows at a time: loads in flight together
+            // kRows rows at a time, their loads in flight together; then the short batch that may remain
+            auto batch = [&](auto full_c, uint32_t nr) {
+                constexpr bool kFull = decltype(full_c)::value;
                 int32_t t8[kRows];
-                uint32_t ph[kRows], kk[kRows];
+                uint32_t kk[kRows];
                 uint2 rc[kRows];
 #pragma unroll
                 for (int q = 0; q < kRows; ++q) {
-                    const uint32_t uq = u + q * W, t = uq >> kLog;
-                    ph[q] = uq + t; kk[q] = uq & (uint32_t)(SUB - 1);
-                    t8[q] = R[ph[q]]; rc[q] = RC[t];
+                    if (kFull || (uint32_t)q < nr) {
+                        const uint32_t uq = u + q * W, t = uq >> kLog;
+                        kk[q] = uq & (uint32_t)(SUB - 1);
+                        t8[q] = R[uq + t]; rc[q] = RC[t];
+                    }
                 }
 #pragma unroll
                 for (int q = 0; q < kRows; ++q) {
-                    acc += t8[q] + ((kk[q] < rc[q].x) ? (int32_t)rc[q].y : 0);
-                    if (kDirect) *reinterpret_cast<float *>(band_out + (off + q * 4u * W)) = (float)(int16_t)acc * s;
-                    else R[ph[q]] = acc;
+                    if (kFull || (uint32_t)q < nr) {
+                        acc += t8[q] + ((kk[q] < rc[q].x) ? (int32_t)rc[q].y : 0);
+                        *reinterpret_cast<float *>(band_out + (off + q * 4u * W)) = (float)(int16_t)acc * s;
+                    }
                 }
+            };
+            uint32_t h = 0;
+            for (; h + kRows <= nrow; h += kRows) {
+                batch(std::true_type{}, (uint32_t)kRows);
                 u += kRows * W;
                 off += 4u * kRows * W;
             }
-            for (; h < nrow; ++h, u += W, off += 4u * W) {
-                const uint32_t t = u >> kLog, ph = u + t;
-                const uint2 rc = RC[t];
-                acc += R[ph] + (((u & (uint32_t)(SUB - 1)) < rc.x) ? (int32_t)rc.y : 0);
-                if (kDirect) *reinterpret_cast<float *>(band_out + off) = (float)(int16_t)acc * s; else R[ph] = acc;
-            }
+            if (h < nrow) batch(std::false_type{}, nrow - h);        // uniform
             return acc;
         };
-        auto walk_all = [&](auto direct_c) {
-            if (pl.big) {
+        if (pl.big) {
 #pragma unroll
-                for (int c = 0; c < kColGroups; ++c) {
-                    const uint32_t col = c * kWave + lane;
-                    if (col < W) colacc[c] = walk(direct_c, col, colacc[c]);
-                }
-            } else {
-                const uint32_t ncols = npl * W;
-                for (uint32_t col = lane; col < ncols; col += kWave) (void)walk(direct_c, col, 0);
+            for (int c = 0; c < kColGroups; ++c) {
+                const uint32_t col = c * kWave + lane;
+                if (col < W) colacc[c] = walk(col, colacc[c]);
             }
-        };
-        if (direct) walk_all(std::true_type{}); else walk_all(std::false_type{});
-
-        // ---- narrow rows: de-quantise and store from LDS, 128 bits at a time ----
-        if (!direct) {
-            wave_sync();
-            const uint32_t q_lo = e0 >> 2, q_hi = (e0 + n + 3) >> 2;       // global quads touched
-            for (uint32_t qd = q_lo + lane; qd < q_hi; qd += kWave) {
-                const uint32_t i = qd << 2;
-                float o[4];
-                bool ok[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const uint32_t e = i + t;
-                    ok[t] = e >= e0 && e - e0 < n;
-                    const uint32_t u = e - base;
-                    o[t] = ok[t] ? (float)R[u + (u >> kLog)] * s : 0.0f;
-                }
-                if (ok[0] && ok[3]) {
-                    *reinterpret_cast<float4 *>(a.xout + i) = make_float4(o[0], o[1], o[2], o[3]);
-                } else {
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) if (ok[t]) a.xout[i + t] = o[t];
-                }
-            }
+        } else {
+            const uint32_t ncols = npl * W;
+            for (uint32_t col = lane; col < ncols; col += kWave) (void)walk(col, 0);
         }
         wave_sync();                                      // R and the staging buffer are reused by the next band
         cur = nxt; fa = fn; sg = sgn; item = nitem; bi = nb;
