@@ -328,21 +328,23 @@ __device__ __forceinline__ uint32_t decode_run(const DecodeTables &T, RD rd, uin
     return 32u * wi - (uint32_t)avail;
 }
 
-// Decoder for a bit stream staged in LDS.  Word k of the stream is S[kStagePad + k]; the words
-// from S[kStagePad - 1] to S[kStagePad + wmax + 2] are readable.  Decodes `count` codewords from
-// bit `pos` on and calls put(k, residual) for k >= skip; returns the bit position after the last
-// codeword.
+// Decoder for a bit stream staged in LDS.  Word k of the stream is S[kStagePad + k].  Decodes
+// `count` codewords from bit `pos` on and calls put(k, residual) for k >= skip; returns the bit
+// position after the last codeword.
 //
 // The 32 bits from position p on are alignbit(S[j], S[j+1], -p mod 32) with j = (p + 31) / 32 - 1
 // (stream words): counted this way the shift stays below 32 also when p is a multiple of 32.
-// A corrupted stream cannot run out of the staged range: word indices are clamped.
+// Word indices are not clamped: a codeword has at most kMaxCodeLen bits, so `count` codewords
+// starting inside the staged words read at most count * kMaxCodeLen / 32 + 3 words past them,
+// whatever the stream holds; the caller's buffer has that many words behind the staged ones
+// (stage_tail_words).
+constexpr uint32_t stage_tail_words(uint32_t count) { return count * kMaxCodeLen / 32 + 4; }
 constexpr int kStagePad = 4;
 template <class PUT>
-__device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint32_t *S, uint32_t wmax, uint32_t pos,
+__device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint32_t *S, uint32_t pos,
                                                uint32_t count, uint32_t skip, PUT put, bool &bad)
 {
     const uint32_t t32 = T.t32, sh = T.sh, has_long = T.has_long;
-    const uint32_t jmax = wmax + 1;
     const char *t1 = reinterpret_cast<const char *>(T.t1);
     // The three stream words around the position live in registers: wa, wb are the window of the
     // current codeword, wc the word after them.  A codeword of the first two table levels is at
@@ -351,7 +353,6 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
     // has to wait for is the table look-up.
     uint32_t npos = 0u - pos;                                 // alignbit takes its shift from -pos mod 32
     uint32_t J = (31u - npos) >> 5;                           // stream word J-1 holds bit pos (or ends just before it)
-    J = J < jmax ? J : jmax;
     uint32_t wa = S[kStagePad - 1 + J], wb = S[kStagePad + J], wc = S[kStagePad + 1 + J];
 #pragma unroll 4
     for (uint32_t k = 0; k < count; ++k) {
@@ -380,13 +381,11 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
                 e = sy | (len << 10);
                 // such a codeword may end two words further on: take the first of the two moves here
                 uint32_t Jf = (31u - (npos - len)) >> 5;
-                Jf = Jf < jmax ? Jf : jmax;
                 if (Jf > J + 1) { wa = wb; wb = wc; wc = S[kStagePad + 2 + J]; ++J; }
             }
         }
         npos -= e >> 10;
         uint32_t Jn = (31u - npos) >> 5;
-        Jn = Jn < jmax ? Jn : jmax;
         const bool moved = Jn != J;
         wa = moved ? wb : wa;
         wb = moved ? wc : wb;

@@ -93,7 +93,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
     __shared__ DecodeTables T;
     __shared__ RT       Rs[kWaves][kBandMax + kND];       // one pad slot per sub-block: lane-conflict free
     __shared__ uint32_t Ps[kWaves][kE * kWave + 2];       // exclusive prefix of sub-block bit counts
-    __shared__ __align__(16) uint32_t Ss[kWaves][kStagePad + kStageWords + 4];   // staged payload; after the decode, the lane records
+    __shared__ __align__(16) uint32_t Ss[kWaves][kStagePad + kStageWords + stage_tail_words(SUB)];   // staged payload and the words a damaged
+                                                                           // stream may read past it; after the decode, the lane records
     static_assert(sizeof(Rs) >= 13 * 1024, "the table build borrows Rs as scratch");
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
                     reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_payload + (uint64_t)uu0 * 16);
                 auto run_decode = [&](uint32_t count, uint32_t skip, auto put) -> uint32_t {
                     if (staged)
-                        return decode_lds(T, S, sg.nq * 4 - 1, spos, count, skip, put, lbad) - spos + start;
+                        return decode_lds(T, S, spos, count, skip, put, lbad) - spos + start;
                     return decode_run<false>(T, [&](uint32_t k) -> uint32_t { return gw[k < last ? k : last]; }, start,
                                              count, skip, put, lbad);
                 };
