@@ -140,6 +140,39 @@ int cmp_compress_batch(cmp_ctx *ctx, int n, const float *const *d_x, const int64
 int cmp_compress_static(int device, const cmp_config *cfg, const float *d_x, const int64_t shape[4], float eb,
                         void *d_out, size_t out_cap, void *stream);
 
+/* Compressed activations of a forward pass, held as a stack in ONE device buffer until the
+ * backward pass pops them in reverse order (Section 4.4: compress when a layer's activation is
+ * saved, keep it in memory, decompress when the backward pass reaches that layer).  Where a
+ * container starts depends on the sizes of all containers before it, which only the GPU knows:
+ * the bookkeeping (top of the stack, one record per slot) therefore lives in device memory, and
+ * none of these calls makes the host wait, except cmp_arena_stats.
+ *   d_state   device memory of cmp_arena_state_bytes(slots) bytes, 16-byte aligned, set up by
+ *             cmp_arena_init (a kernel on `stream`);
+ *   d_arena   the buffer of the containers, 256-byte aligned, arena_cap bytes;
+ *   slot      which record a push fills and a pop reads: the caller numbers its pushes 0, 1, 2, ...
+ *             and reuses a number only after the slots at and above it have been popped.
+ * cmp_arena_push compresses d_x (as cmp_compress does) to the top of the stack and records the
+ * container in `slot`; if it does not fit, the slot stays empty and the state counts a failure
+ * (also reported by cmp_last_status as CMP_E_NOSPACE).  cmp_arena_pop decompresses the container of
+ * `slot` into d_xout (as cmp_decompress does) and gives the slot back: the space returns to the
+ * stack as soon as every slot above it has been popped too, so pops in reverse push order keep the
+ * stack compact, and a pop out of order leaves a hole until then.  An empty slot pops as a
+ * malformed container (CMP_E_FORMAT from cmp_last_status).  Empty tensors and shapes whose
+ * planes are larger than one band of the decoder (about 2000 elements) with rows wider than 256
+ * are refused by push and pop (CMP_E_ARG; cmp_arena_accepts tells beforehand, 1 = accepted): keep
+ * such tensors outside the arena.  All calls that use one d_state must be issued on one stream.
+ * cmp_arena_stats waits for `stream` and stores the bytes in use, their peak, the slots held and
+ * the pushes that failed (any pointer may be NULL); it returns CMP_E_NOSPACE if any push failed. */
+size_t cmp_arena_state_bytes(uint32_t slots);
+int cmp_arena_accepts(const cmp_ctx *ctx, const int64_t shape[4]);
+int cmp_arena_init(cmp_ctx *ctx, void *d_state, uint32_t slots, void *stream);
+int cmp_arena_push(cmp_ctx *ctx, void *d_arena, size_t arena_cap, void *d_state, uint32_t slot, const float *d_x,
+                   const int64_t shape[4], float eb, void *stream);
+int cmp_arena_pop(cmp_ctx *ctx, const void *d_arena, void *d_state, uint32_t slot, const int64_t shape[4], float eb,
+                  float *d_xout, void *stream);
+int cmp_arena_stats(cmp_ctx *ctx, const void *d_state, uint64_t *h_top, uint64_t *h_peak, uint32_t *h_held,
+                    uint32_t *h_failed, void *stream);
+
 /* cmp_compress in two calls, for callers that pipeline tensors over several streams: the single
  * workgroup that builds the Huffman codebook leaves the GPU idle, and with begin(i+1) issued on
  * one stream while finish(i) runs on another the first sweep of the next tensor fills that time.

@@ -23,7 +23,8 @@ CMP_STAGE_OUTLIER_IDX, CMP_STAGE_OUTLIER_VAL = 4, 5
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
            "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",
            "cmp_profile", "cmp_profile_read", "cmp_default_controller_config", "cmp_estimate_eb",
-           "cmp_compress_begin", "cmp_compress_finish", "cmp_compress_batch", "cmp_decompress_batch", "cmp_compress_static"]
+           "cmp_compress_begin", "cmp_compress_finish", "cmp_compress_batch", "cmp_decompress_batch", "cmp_compress_static",
+           "cmp_arena_state_bytes", "cmp_arena_accepts", "cmp_arena_init", "cmp_arena_push", "cmp_arena_pop", "cmp_arena_stats"]
 
 
 class cmp_controller_config(C.Structure):
@@ -36,6 +37,7 @@ class cmp_config(C.Structure):
 
 
 _lib = None
+sync_calls = 0        # calls made through this module that wait for the GPU (for tests of asynchrony)
 
 
 def lib() -> C.CDLL:
@@ -61,6 +63,12 @@ def lib() -> C.CDLL:
         L.cmp_compress_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]; L.cmp_compress_batch.restype = i32
         L.cmp_decompress_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]; L.cmp_decompress_batch.restype = i32
         L.cmp_compress_static.argtypes = [i32, vp, vp, vp, C.c_float, vp, sz, vp]; L.cmp_compress_static.restype = i32
+        L.cmp_arena_state_bytes.argtypes = [C.c_uint32]; L.cmp_arena_state_bytes.restype = sz
+        L.cmp_arena_accepts.argtypes = [vp, vp]; L.cmp_arena_accepts.restype = i32
+        L.cmp_arena_init.argtypes = [vp, vp, C.c_uint32, vp]; L.cmp_arena_init.restype = i32
+        L.cmp_arena_push.argtypes = [vp, vp, sz, vp, C.c_uint32, vp, vp, C.c_float, vp]; L.cmp_arena_push.restype = i32
+        L.cmp_arena_pop.argtypes = [vp, vp, vp, C.c_uint32, vp, C.c_float, vp, vp]; L.cmp_arena_pop.restype = i32
+        L.cmp_arena_stats.argtypes = [vp, vp, vp, vp, vp, vp, vp]; L.cmp_arena_stats.restype = i32
         L.cmp_compress_begin.argtypes = [vp, vp, vp, C.c_float, vp]; L.cmp_compress_begin.restype = i32
         L.cmp_compress_finish.argtypes = [vp, vp, sz, vp, vp]; L.cmp_compress_finish.restype = i32
         L.cmp_default_controller_config.argtypes = [vp]; L.cmp_default_controller_config.restype = None
@@ -100,6 +108,8 @@ def cmp_bound(ctx, shape) -> int:
 
 
 def cmp_compress(ctx, d_x: int, shape, eb: float, d_out: int, out_cap: int, want_size: bool, stream: int):
+    global sync_calls
+    sync_calls += 1 if want_size else 0
     s = _shape4(shape)
     size = C.c_size_t(0)
     rc = lib().cmp_compress(ctx, d_x, C.addressof(s), C.c_float(eb), d_out, out_cap,
@@ -132,6 +142,8 @@ def cmp_compress_static(device: int, cfg: "cmp_config | None", d_x: int, shape, 
 
 
 def cmp_compressed_size(ctx, d_buf: int, stream: int):
+    global sync_calls
+    sync_calls += 1
     size = C.c_size_t(0)
     rc = lib().cmp_compressed_size(ctx, d_buf, C.addressof(size), stream)
     return rc, int(size.value)
@@ -165,7 +177,43 @@ def cmp_decompress_batch(ctx, d_bufs, sizes, shapes, ebs, d_xouts, stream: int) 
     return lib().cmp_decompress_batch(ctx, n, bufs, sz, sh, eb, outs, stream)
 
 
+def cmp_arena_state_bytes(slots: int) -> int:
+    return int(lib().cmp_arena_state_bytes(slots))
+
+
+def cmp_arena_accepts(ctx, shape) -> bool:
+    s = _shape4(shape)
+    return bool(lib().cmp_arena_accepts(ctx, C.addressof(s)))
+
+
+def cmp_arena_init(ctx, d_state: int, slots: int, stream: int) -> int:
+    return lib().cmp_arena_init(ctx, d_state, slots, stream)
+
+
+def cmp_arena_push(ctx, d_arena: int, arena_cap: int, d_state: int, slot: int, d_x: int, shape, eb: float, stream: int) -> int:
+    s = _shape4(shape)
+    return lib().cmp_arena_push(ctx, d_arena, arena_cap, d_state, slot, d_x, C.addressof(s), C.c_float(eb), stream)
+
+
+def cmp_arena_pop(ctx, d_arena: int, d_state: int, slot: int, shape, eb: float, d_xout: int, stream: int) -> int:
+    s = _shape4(shape)
+    return lib().cmp_arena_pop(ctx, d_arena, d_state, slot, C.addressof(s), C.c_float(eb), d_xout, stream)
+
+
+def cmp_arena_stats(ctx, d_state: int, stream: int):
+    """Waits for the stream.  Returns (rc, top, peak, slots held, pushes failed)."""
+    global sync_calls
+    sync_calls += 1
+    top, peak = C.c_uint64(0), C.c_uint64(0)
+    held, failed = C.c_uint32(0), C.c_uint32(0)
+    rc = lib().cmp_arena_stats(ctx, d_state, C.addressof(top), C.addressof(peak), C.addressof(held), C.addressof(failed),
+                               stream)
+    return rc, int(top.value), int(peak.value), int(held.value), int(failed.value)
+
+
 def cmp_last_status(ctx, stream: int) -> int:
+    global sync_calls
+    sync_calls += 1
     return lib().cmp_last_status(ctx, stream)
 
 

@@ -422,6 +422,108 @@ int cmp_compress_static(int device, const cmp_config *cfg, const float *d_x, con
     return CMP_OK;
 }
 
+// ---- a stack of containers whose bookkeeping stays on the device --------------------------------
+size_t cmp_arena_state_bytes(uint32_t slots)
+{
+    return sizeof(ArenaState) + (size_t)(slots ? slots - 1 : 0) * sizeof(ArenaSlot);
+}
+
+int cmp_arena_accepts(const cmp_ctx *ctx, const int64_t shape[4])
+{
+    uint64_t numel;
+    if (!ctx || !shape_numel(shape, &numel) || numel == 0 || numel > ctx->cfg.max_numel) return 0;
+    TensorD t;
+    std::memset(&t, 0, sizeof(t));
+    for (int k = 0; k < 4; ++k) t.shape[k] = (uint32_t)shape[k];
+    t.numel = (uint32_t)numel;
+    return plan_decode_fused(&t, ctx->cfg.sub) ? 1 : 0;
+}
+
+int cmp_arena_init(cmp_ctx *ctx, void *d_state, uint32_t slots, void *stream)
+{
+    if (!ctx || !d_state || slots == 0 || (reinterpret_cast<uintptr_t>(d_state) & 15)) return CMP_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    launch_arena_init(static_cast<ArenaState *>(d_state), slots, static_cast<hipStream_t>(stream));
+    return hipGetLastError() == hipSuccess ? CMP_OK : CMP_E_HIP;
+}
+
+int cmp_arena_push(cmp_ctx *ctx, void *d_arena, size_t arena_cap, void *d_state, uint32_t slot, const float *d_x,
+                   const int64_t shape[4], float eb, void *stream)
+{
+    if (!ctx || !d_arena || !d_state || (reinterpret_cast<uintptr_t>(d_arena) & (kArenaAlign - 1))) return CMP_E_ARG;
+    if (ctx->has_pending) return CMP_E_ARG;
+    CheckedTensor ck;
+    const int rc = check_tensor(ctx->cfg, d_x, shape, eb, &ck);
+    if (rc != CMP_OK) return rc;
+    if (!cmp_arena_accepts(ctx, shape)) return CMP_E_ARG;      // what cmp_arena_pop could not take back
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    BatchC b;
+    group_begin(&b, ctx->cfg, ctx->s);
+    group_add(&b, ck, d_arena, arena_cap);
+    b.t[0].arena = static_cast<const ArenaState *>(d_state);
+    group_plan_sweep(&b);
+    group_launch_begin(b, &ctx->prof, st);
+    group_launch_finish(b, &ctx->prof, st);
+    launch_arena_pushed(b, static_cast<ArenaState *>(d_state), slot, st);
+    ctx->last_numel = b.t[0].numel;
+    ctx->last_out = nullptr;                                   // its place is known to the GPU only
+    return hipGetLastError() == hipSuccess ? CMP_OK : CMP_E_HIP;
+}
+
+int cmp_arena_pop(cmp_ctx *ctx, const void *d_arena, void *d_state, uint32_t slot, const int64_t shape[4], float eb,
+                  float *d_xout, void *stream)
+{
+    uint64_t numel;
+    float s, r;
+    if (!ctx || !d_arena || !d_state || !shape_numel(shape, &numel)) return CMP_E_ARG;
+    if (numel > ctx->cfg.max_numel || (numel > 0 && !d_xout)) return CMP_E_ARG;
+    if (!constants(eb, ctx->cfg.guard_shift, &s, &r)) return CMP_E_ARG;
+    if (reinterpret_cast<uintptr_t>(d_xout) & 15) return CMP_E_ARG;
+    BatchD b;
+    std::memset(&b, 0, sizeof(b));
+    b.n = 1;
+    b.radius = ctx->cfg.radius; b.sub = ctx->cfg.sub; b.guard_shift = ctx->cfg.guard_shift;
+    b.meta = ctx->s.meta; b.status = ctx->s.status;
+    TensorD &t = b.t[0];
+    t.buf = static_cast<const uint8_t *>(d_arena);
+    t.size = 0;
+    t.slot = static_cast<const ArenaState *>(d_state)->slot + slot;      // address arithmetic only: a device pointer
+    t.xout = d_xout;
+    for (int k = 0; k < 4; ++k) t.shape[k] = (uint32_t)shape[k];
+    t.numel = (uint32_t)numel;
+    std::memcpy(&t.eb_bits, &eb, 4);
+    t.s = s;
+    // the kernels for shapes outside the fused kernel's plan take their arguments from the host,
+    // which does not know where the container lies
+    if (!plan_decode_fused(&t, ctx->cfg.sub)) return CMP_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    launch_decode_fused(b, &ctx->prof, st);
+    launch_arena_release(static_cast<ArenaState *>(d_state), slot, st);
+    return hipGetLastError() == hipSuccess ? CMP_OK : CMP_E_HIP;
+}
+
+int cmp_arena_stats(cmp_ctx *ctx, const void *d_state, uint64_t *h_top, uint64_t *h_peak, uint32_t *h_held,
+                    uint32_t *h_failed, void *stream)
+{
+    if (!ctx || !d_state) return CMP_E_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return CMP_E_HIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ArenaState hd;
+    if (hipMemcpyAsync(&hd, d_state, sizeof(hd), hipMemcpyDeviceToHost, st) != hipSuccess) return CMP_E_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return CMP_E_HIP;
+    if (h_top) *h_top = hd.top;
+    if (h_peak) *h_peak = hd.peak;
+    if (h_held) *h_held = hd.nslots;
+    if (h_failed) *h_failed = hd.failed;
+    return hd.failed ? CMP_E_NOSPACE : CMP_OK;
+}
+
 int cmp_compress_begin(cmp_ctx *ctx, const float *d_x, const int64_t shape[4], float eb, void *stream)
 {
     if (!ctx) return CMP_E_ARG;

@@ -28,7 +28,8 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
     // one workgroup per tensor of the group
     const uint32_t ti = blockIdx.x;
     uint32_t *__restrict__ g_hist = b.hist + (uint64_t)ti * kHistCopies * kMaxSym;
-    uint8_t *__restrict__ out = b.t[ti].out;
+    const OutRef oref = resolve_out(b.t[ti]);
+    uint8_t *__restrict__ out = oref.out;
     __shared__ uint64_t key[kMaxSym];            // used symbols, compacted: count << 10 | symbol
     __shared__ uint32_t leaf_w[kMaxSym + 192];   // leaf weights, ascending, padded with kInf
     __shared__ uint16_t leaf_sym[kMaxSym];
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
     b.enc32[ti * kMaxSym + tid] = (L && L <= 27u) ? (((uint32_t)entry << (32u - L)) | L) : 0u;
     // container section `lens`: 2*radius bytes, zero padded to a multiple of 16
     const uint32_t padded = (nsym + 15u) & ~15u;
-    if ((uint32_t)tid < padded) out[kHeaderBytes + tid] = ((uint32_t)tid < nsym) ? (uint8_t)L : 0;
+    if ((uint32_t)tid < padded && oref.cap >= kHeaderBytes + padded) out[kHeaderBytes + tid] = ((uint32_t)tid < nsym) ? (uint8_t)L : 0;
     if (tid == 0) b.tmeta[ti].max_len = max_len_s;
 }
 

@@ -106,6 +106,12 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
     const DecompressArgs a = decompress_args(b, td);
     FusedPlan pl;
     pl.big = td.big; pl.G = td.G; pl.Rb = td.Rb; pl.nitems = td.nitems; pl.divW = td.divW;
+    // a container on the device-side stack: an empty slot, or one too short for the sections of fixed
+    // size, is not looked at (the host has checked this for containers it knows the size of)
+    if (td.slot && a.size < a.lay.off_payload) {
+        if (blockIdx.x == td.wg_base && tid == 0) atomicOr(a.status, kStFormat);
+        return;
+    }
     // every workgroup validates the container and builds the decode tables for itself
     {
         const uint32_t defect = build_tables_256(T, a, reinterpret_cast<uint32_t *>(&Rs[0][0]));

@@ -12,156 +12,26 @@ namespace {
 
 constexpr int      kThreads  = 256;
 constexpr int      kDecThreads = 128;              // sub-blocks (lanes) per decode workgroup
-__device__ __forceinline__ uint64_t align16(uint64_t v) { return (v + 15) & ~15ull; }
 
 // ---------------------------------------------------------------------------
-// Validation of the header and the code lengths, and the decode tables.
-// One workgroup of 1024 threads.  On failure meta[kMetaBad] = 1 and every later
-// kernel of the call returns at once.
+// Validation of the header and the code lengths, and the decode tables, for the
+// kernels below: the same routine the fused kernel runs in every workgroup, here
+// in a workgroup of its own that leaves the tables in global memory.  On failure
+// meta[kMetaBad] = 1 and every later kernel of the call returns at once.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_decode_tables(DecompressArgs a, DecodeTables *tb)
+__global__ __launch_bounds__(256) void k_decode_tables(DecompressArgs a, DecodeTables *tb)
 {
     __shared__ DecodeTables T;
-    __shared__ uint32_t wave_cnt[16][64];
-    __shared__ uint32_t bl_count[64];
-    __shared__ uint64_t first_code[64];
-    __shared__ uint32_t offs[64];
-    __shared__ uint32_t bad_s, used_s, max_len_s;
-    __shared__ unsigned long long kraft_s;      // in units of 2^-56
+    __shared__ uint32_t scratch[3584];               // 14 KB, what build_tables_256 asks for
     const int tid = threadIdx.x;
-    const uint32_t nsym = 2 * a.radius;
-    // the header and the four table ends are fetched by separate lanes in one round trip
-    __shared__ Header hd_s;
-    __shared__ uint32_t ends_s[4];
-    if (tid < (int)(kHeaderBytes / 4)) reinterpret_cast<uint32_t *>(&hd_s)[tid] = reinterpret_cast<const uint32_t *>(a.buf)[tid];
-    if (tid >= 64 && tid < 68) {
-        const uint32_t *chunk_off = reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_chunk_off);
-        const uint32_t *outl_off = reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_outl_off);
-        const int k = tid - 64;
-        ends_s[k] = (k == 0) ? chunk_off[0] : (k == 1) ? chunk_off[a.lay.nchunks] : (k == 2) ? outl_off[0] : outl_off[a.lay.nchunks];
-    }
-    __syncthreads();
-    const Header *hd = &hd_s;
-
-    if (tid == 0) {
-        uint32_t bad = 0;
-        const Layout &l = a.lay;
-        if (hd->magic != kMagic || hd->version != kVersion || hd->status != 0) bad = kStFormat;
-        for (int k = 0; k < 112 && !bad; ++k) if (hd->zero[k]) bad = kStFormat;
-        if (!bad) {
-            if (hd->eb_bits != a.eb_bits) bad = kStMismatch;
-            for (int k = 0; k < 4; ++k) if (hd->shape[k] != a.shape[k]) bad = kStMismatch;
-            if (hd->radius != a.radius || hd->chunk != kChunk || hd->sub != a.sub ||
-                hd->guard_shift != a.guard_shift) bad = kStMismatch;
-        }
-        if (!bad) {
-            const uint64_t n_out = hd->n_outliers;
-            const uint64_t sect = align16(4 * n_out);
-            if (hd->numel != a.numel || hd->nchunks != l.nchunks) bad = kStFormat;
-            else if (hd->off_lens != l.off_lens || hd->off_chunk_off != l.off_chunk_off ||
-                     hd->off_outl_off != l.off_outl_off || hd->off_sub_bits != l.off_sub_bits ||
-                     hd->off_payload != l.off_payload) bad = kStFormat;
-            else if (hd->total_size > a.size || n_out > a.numel || hd->range_events > a.numel) bad = kStFormat;
-            else if (hd->off_outl_idx < l.off_payload || ((hd->off_outl_idx - l.off_payload) & 15)) bad = kStFormat;
-            else if (hd->off_outl_val != hd->off_outl_idx + sect || hd->total_size != hd->off_outl_val + sect)
-                bad = kStFormat;
-            else if (((hd->off_outl_idx - l.off_payload) >> 4) >= (1ull << 32)) bad = kStFormat;
-            if (!bad) {
-                const uint32_t units = (uint32_t)((hd->off_outl_idx - l.off_payload) >> 4);
-                if (ends_s[0] != 0 || ends_s[1] != units) bad = kStFormat;
-                if (ends_s[2] != 0 || ends_s[3] != (uint32_t)n_out) bad = kStFormat;
-                T.payload_units = units;
-                T.n_outliers = (uint32_t)n_out;
-            }
-        }
-        bad_s = bad; used_s = 0; max_len_s = 0; kraft_s = 0;
-    }
-    if (tid < 64) { bl_count[tid] = 0; first_code[tid] = 0; offs[tid] = 0; }
-    __syncthreads();
-    if (bad_s) {
-        if (tid == 0) { a.meta[kMetaBad] = 1; atomicOr(a.status, bad_s); }
+    const uint32_t defect = build_tables_256(T, a, scratch);
+    if (defect) {
+        if (tid == 0) { a.meta[kMetaBad] = 1; atomicOr(a.status, defect); }
         return;
     }
-
-    // code lengths: range, Kraft sum, maximum
-    uint32_t L = 0;
-    if ((uint32_t)tid < nsym) L = a.buf[a.lay.off_lens + tid];
-    else if ((uint32_t)tid < ((nsym + 15u) & ~15u)) { if (a.buf[a.lay.off_lens + tid]) atomicOr(&bad_s, kStFormat); }
-    if (L > kMaxCodeLen) { atomicOr(&bad_s, kStFormat); L = 0; }
-    if (L) {
-        atomicAdd(&used_s, 1u);
-        atomicAdd(&kraft_s, 1ull << (56 - L));
-        atomicMax(&max_len_s, L);
-        atomicAdd(&bl_count[L], 1u);
-    }
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned long long one = 1ull << 56;
-        if (used_s >= 2 && kraft_s != one) bad_s |= kStFormat;
-        if (used_s == 1 && max_len_s != 1) bad_s |= kStFormat;
-        if (used_s == 0 && a.numel != 0) bad_s |= kStFormat;
-        if (hd->max_len != max_len_s) bad_s |= kStFormat;
-        uint64_t code = 0;
-        uint32_t o = 0;
-        for (int k = 1; k < 64; ++k) {
-            code = (code + (uint64_t)(k > 1 ? bl_count[k - 1] : 0u)) << 1;
-            first_code[k] = code;
-            offs[k] = o;
-            o += bl_count[k];
-        }
-        // left-aligned end of the codes of at most kLB bits, and the level-2 geometry
-        const uint64_t t = (first_code[kLB] + bl_count[kLB]) << (32 - kLB);
-        const uint64_t span = (1ull << 32) - t;              // code space of the longer codes
-        uint32_t sh = 0;
-        while ((span >> sh) > kT2Size) ++sh;
-        T.t32 = (uint32_t)t; T.sh = sh; T.has_long = (max_len_s > kLB && span > 0) ? 1u : 0u;
-        T.max_len = max_len_s;
-    }
-    __syncthreads();
-    if (bad_s) {
-        if (tid == 0) { a.meta[kMetaBad] = 1; atomicOr(a.status, bad_s); }
-        return;
-    }
-
-    // symbols ordered by (length, symbol)
-    const uint32_t rank = rank_within_length(L, wave_cnt, tid);
-    if (L) T.sorted[offs[L] + rank] = (uint16_t)(((uint32_t)tid - a.radius) & 1023u);   // as a residual
-    if (tid < 64) { T.first[tid] = first_code[tid]; T.count[tid] = bl_count[tid]; T.offs[tid] = offs[tid]; }
-    __syncthreads();
-
-    // level 1: entry idx is the codeword (if any, of at most kLB bits) that prefixes idx
-    for (uint32_t idx = tid; idx < kT1Size; idx += 1024) {
-        uint32_t e = 0;
-        for (uint32_t l = 1; l <= kLB; ++l) {
-            const uint32_t code = idx >> (kLB - l);
-            const uint32_t f = (uint32_t)first_code[l];
-            if (code >= f && code - f < bl_count[l]) { e = T.sorted[offs[l] + code - f] | (l << 10); break; }
-        }
-        T.t1[idx] = (uint16_t)e;
-    }
-    // level 2: entry i covers left-aligned values t32 + [i << sh, (i+1) << sh)
-    if ((uint32_t)tid < kT2Size) {
-        const uint32_t idx = tid;
-        uint32_t e = 0;
-        const uint64_t v = (uint64_t)T.t32 + ((uint64_t)idx << T.sh);
-        if (T.has_long && v < (1ull << 32)) {
-            const uint32_t lmax = (32 - T.sh < T.max_len) ? 32 - T.sh : T.max_len;
-            for (uint32_t l = kLB + 1; l <= lmax; ++l) {
-                const uint64_t code = v >> (32 - l);
-                if (code >= first_code[l] && code - first_code[l] < bl_count[l]) {
-                    e = T.sorted[offs[l] + (uint32_t)(code - first_code[l])] | (l << 10);
-                    break;
-                }
-            }
-        }
-        T.t2[idx] = (uint16_t)e;
-    }
-    __syncthreads();
-    {
-        const uint32_t *src = reinterpret_cast<const uint32_t *>(&T);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(tb);
-        for (uint32_t k = tid; k < sizeof(DecodeTables) / 4; k += 1024) dst[k] = src[k];
-    }
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(&T);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(tb);
+    for (uint32_t k = tid; k < sizeof(DecodeTables) / 4; k += 256) dst[k] = src[k];
     if (tid == 0) a.meta[kMetaBad] = 0;
 }
 
@@ -292,7 +162,7 @@ size_t decode_tables_bytes() { return sizeof(DecodeTables); }
 void launch_decompress_unfused(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st)
 {
     DecodeTables *tb = static_cast<DecodeTables *>(tables);
-    launch(prof, kKDecodeTables, k_decode_tables, dim3(1), dim3(1024), st, a, tb);
+    launch(prof, kKDecodeTables, k_decode_tables, dim3(1), dim3(256), st, a, tb);
     if (a.numel == 0) return;
     const DecodeTables *ctb = tb;
     const uint64_t nsubs = (uint64_t)a.lay.nchunks * a.lay.nsub;

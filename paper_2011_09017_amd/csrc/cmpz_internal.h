@@ -104,10 +104,25 @@ enum MetaWord : int {
 constexpr int      kBatchMax   = 24;        // tensors per launch group (kernel arguments hold their descriptors)
 constexpr uint32_t kPackChunks = 16;        // chunks per workgroup of the bit-count and packing kernels
 
+// A stack of containers in one device buffer whose bookkeeping lives on the device: where the
+// next container goes is known to the GPU only (it depends on the sizes of the containers before
+// it), so the host can push tensor after tensor without ever waiting (cmp_arena_* in cmpz.h).
+struct ArenaSlot { uint64_t offset, size; };   // size 0: not held (never pushed, failed, or popped)
+struct ArenaState {
+    uint64_t top;          // bytes in use: where the next container starts
+    uint64_t peak;         // largest `top` so far
+    uint32_t nslots;       // slots pushed and not yet given back (slots are numbered in push order)
+    uint32_t failed;       // pushes that did not fit
+    uint32_t slots_cap, pad;
+    ArenaSlot slot[1];     // [slots_cap]
+};
+constexpr uint64_t kArenaAlign = 256;          // containers start at multiples of this
+
 struct TensorC {
     const float *x;
     uint8_t     *out;
     uint64_t     out_cap;
+    const ArenaState *arena;    // not NULL: the container goes to out + arena->top (out_cap counts from out)
     uint32_t     shape[4];
     uint32_t     numel, nchunks, chunk_base, eb_bits;
     float        r;
@@ -125,7 +140,18 @@ struct TensorMeta {
     uint32_t total_units;       // payload size in 16-byte units
     uint32_t pad;
     uint64_t total_bits;
+    uint64_t total_size;        // container bytes
 };
+
+// Where the container of a tensor goes and how much room there is.
+struct OutRef { uint8_t *out; uint64_t cap; };
+__device__ __forceinline__ OutRef resolve_out(const TensorC &tc)
+{
+    uint64_t at = tc.arena ? tc.arena->top : 0;
+    if (at > tc.out_cap) at = tc.out_cap;
+    OutRef o = {tc.out + at, tc.out_cap - at};
+    return o;
+}
 
 struct BatchC {
     uint32_t n;                 // tensors of this launch group
@@ -170,6 +196,8 @@ struct DecompressArgs {
 struct TensorD {
     const uint8_t *buf;
     uint64_t       size;
+    const ArenaSlot *slot;                  // not NULL (fused kernel only): the container is at buf + slot->offset,
+                                            // slot->size bytes
     float         *xout;
     uint32_t       shape[4];
     uint32_t       numel, eb_bits;
@@ -192,6 +220,9 @@ __host__ __device__ inline DecompressArgs decompress_args(const BatchD &b, const
 {
     DecompressArgs a;
     a.buf = t.buf; a.size = t.size; a.xout = t.xout;
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (t.slot) { a.buf = t.buf + t.slot->offset; a.size = t.slot->size; }
+#endif
     a.numel = t.numel; a.planes = t.shape[0] * t.shape[1];
     a.H = t.shape[2]; a.W = t.shape[3]; a.HW = a.H * a.W;
     for (int i = 0; i < 4; ++i) a.shape[i] = t.shape[i];
@@ -338,6 +369,9 @@ bool sweep1_tiled_fits(uint32_t W);
 void launch_codebook(const BatchC &b, Profiler *prof, hipStream_t st);
 void launch_pack(const BatchC &b, Profiler *prof, hipStream_t st);
 void launch_clear(const BatchC &b, Profiler *prof, hipStream_t st);
+void launch_arena_init(ArenaState *st_dev, uint32_t slots, hipStream_t st);
+void launch_arena_pushed(const BatchC &b, ArenaState *st_dev, uint32_t slot, hipStream_t st);
+void launch_arena_release(ArenaState *st_dev, uint32_t slot, hipStream_t st);
 void launch_widen(uint16_t *sym, uint32_t *wide, uint32_t sym_off, uint32_t nchunks, hipStream_t st);
 size_t decode_tables_bytes();
 bool plan_decode_fused(TensorD *t, uint32_t sub);

@@ -72,7 +72,9 @@ __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
     const uint8_t *L = reinterpret_cast<const uint8_t *>(lens_s);
     const uint16_t *__restrict__ sym = b.sym + (uint64_t)tc.chunk_base * kChunk;
     const Layout lay = make_layout(numel, b.radius, b.sub);
-    uint16_t *__restrict__ sub_bits = reinterpret_cast<uint16_t *>(tc.out + lay.off_sub_bits);
+    const OutRef oref = resolve_out(tc);
+    const bool fixed_fit = oref.cap >= lay.off_payload;              // room for the sections of fixed size (uniform)
+    uint16_t *__restrict__ sub_bits = reinterpret_cast<uint16_t *>(oref.out + lay.off_sub_bits);
 
     for (uint32_t q = wv; q < nq; q += kWaves) {
         const uint32_t c = c0 + q;
@@ -86,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
             // the first lane of a sub-block sits group-1 lanes below its last lane, in the same DPP row
             const uint32_t first_exc = (group == 16) ? dpp_u32<0x11F, 0xf>(exc) : (group == 8) ? dpp_u32<0x117, 0xf>(exc)
                                      : (group == 4)  ? dpp_u32<0x113, 0xf>(exc) : dpp_u32<0x111, 0xf>(exc);
-            if (((uint32_t)lane & (group - 1)) == group - 1)
+            if (fixed_fit && ((uint32_t)lane & (group - 1)) == group - 1)
                 sub_bits[(uint64_t)c * lay.nsub + first_sub + (uint32_t)lane / group] = (uint16_t)(inc - first_exc);
             chunk_bits += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
         };
@@ -210,20 +212,24 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(BatchC b)
     const uint64_t sect = (4 * n_out + 15) & ~15ull;
     const uint64_t off_outl_val = off_outl_idx + sect;
     const uint64_t total = off_outl_val + sect;
-    const bool fits = total <= tc.out_cap;
+    const OutRef oref = resolve_out(tc);
+    const bool fixed_fit = oref.cap >= lay.off_payload;
+    const bool fits = total <= oref.cap;
     const uint32_t range_events = tm.range_events;
 
     // end markers and zero padding of the two offset tables (the fixed sections always fit)
-    uint32_t *chunk_off = reinterpret_cast<uint32_t *>(tc.out + lay.off_chunk_off);
-    uint32_t *outl_off = reinterpret_cast<uint32_t *>(tc.out + lay.off_outl_off);
+    uint32_t *chunk_off = reinterpret_cast<uint32_t *>(oref.out + lay.off_chunk_off);
+    uint32_t *outl_off = reinterpret_cast<uint32_t *>(oref.out + lay.off_outl_off);
     const uint32_t padded = (tc.nchunks + 1 + 3) & ~3u;
-    chunk_off[tc.nchunks] = (uint32_t)total_units;
-    outl_off[tc.nchunks] = (uint32_t)n_out;
-    for (uint32_t k = tc.nchunks + 1; k < padded; ++k) { chunk_off[k] = 0; outl_off[k] = 0; }
+    if (fixed_fit) {
+        chunk_off[tc.nchunks] = (uint32_t)total_units;
+        outl_off[tc.nchunks] = (uint32_t)n_out;
+        for (uint32_t k = tc.nchunks + 1; k < padded; ++k) { chunk_off[k] = 0; outl_off[k] = 0; }
+    }
     if (fits) {
         // zero padding of both outlier sections
-        uint32_t *oidx = reinterpret_cast<uint32_t *>(tc.out + off_outl_idx);
-        uint32_t *oval = reinterpret_cast<uint32_t *>(tc.out + off_outl_val);
+        uint32_t *oidx = reinterpret_cast<uint32_t *>(oref.out + off_outl_idx);
+        uint32_t *oval = reinterpret_cast<uint32_t *>(oref.out + off_outl_val);
         for (uint64_t k = n_out; k < ((n_out + 3) & ~3ull); ++k) { oidx[k] = 0; oval[k] = 0; }
     }
 
@@ -242,8 +248,8 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(BatchC b)
     hd.off_outl_off = lay.off_outl_off; hd.off_sub_bits = lay.off_sub_bits;
     hd.off_payload = lay.off_payload; hd.off_outl_idx = off_outl_idx;
     hd.off_outl_val = off_outl_val; hd.total_size = total;
-    uint32_t *dst = reinterpret_cast<uint32_t *>(tc.out);
-    for (uint32_t k = 0; k < kHeaderBytes / 4; ++k) dst[k] = raw[k];
+    uint32_t *dst = reinterpret_cast<uint32_t *>(oref.out);
+    if (fixed_fit) for (uint32_t k = 0; k < kHeaderBytes / 4; ++k) dst[k] = raw[k];
 
     uint32_t st = 0;
     if (!fits) st |= kStNoSpace;
@@ -253,6 +259,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(BatchC b)
     tm.n_outliers = (uint32_t)n_out;
     tm.total_units = (uint32_t)total_units;
     tm.total_bits = bits_s;
+    tm.total_size = total;
     tm.range_events = 0;                             // ready for the next call
 }
 
@@ -284,6 +291,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
     const uint32_t numel = tc.numel;
     const bool short_codes = tm.max_len <= kShortMax;                // uniform
     const Layout lay = make_layout(numel, b.radius, b.sub);
+    uint8_t *const out = resolve_out(tc).out;
 
     uint32_t *table32 = reinterpret_cast<uint32_t *>(table);
     if (short_codes) {
@@ -305,8 +313,8 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
         const uint32_t cu = b.range_units[blockIdx.x] + wave_inclusive_sum(units) - units;
         const uint32_t co = b.range_outl[blockIdx.x] + wave_inclusive_sum(oc) - oc;
         if (lane < (int)nq) {
-            reinterpret_cast<uint32_t *>(tc.out + lay.off_chunk_off)[c0 + lane] = cu;
-            reinterpret_cast<uint32_t *>(tc.out + lay.off_outl_off)[c0 + lane] = co;
+            reinterpret_cast<uint32_t *>(out + lay.off_chunk_off)[c0 + lane] = cu;
+            reinterpret_cast<uint32_t *>(out + lay.off_outl_off)[c0 + lane] = co;
             coff_s[lane] = cu; bits_s[lane] = bits;
         }
         if (lane <= (int)nq && lane <= (int)kPackChunks) ooff_s[lane] = co;      // lane nq: the end of the last chunk's records
@@ -317,10 +325,10 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
     const uint16_t *__restrict__ sym = b.sym + (uint64_t)tc.chunk_base * kChunk;
     const float *__restrict__ x = tc.x;
     const uint32_t W = tc.shape[3], HW = tc.shape[2] * W;
-    uint4 *__restrict__ payload = reinterpret_cast<uint4 *>(tc.out + lay.off_payload);
+    uint4 *__restrict__ payload = reinterpret_cast<uint4 *>(out + lay.off_payload);
     const uint64_t off_outl_idx = lay.off_payload + (uint64_t)tm.total_units * 16;
-    uint32_t *__restrict__ oidx = reinterpret_cast<uint32_t *>(tc.out + off_outl_idx);
-    int32_t *__restrict__ oval = reinterpret_cast<int32_t *>(tc.out + off_outl_idx + ((4ull * tm.n_outliers + 15) & ~15ull));
+    uint32_t *__restrict__ oidx = reinterpret_cast<uint32_t *>(out + off_outl_idx);
+    int32_t *__restrict__ oval = reinterpret_cast<int32_t *>(out + off_outl_idx + ((4ull * tm.n_outliers + 15) & ~15ull));
     bool failed = false;
 
     for (uint32_t q = wv; q < nq; q += kWaves) {
@@ -513,7 +521,53 @@ __global__ __launch_bounds__(64) void k_widen(uint16_t *sym, uint32_t *wide, uin
     if (lane == 0) wide[qd] = 1;
 }
 
+// ---- the stack of containers (one thread each: a few words of bookkeeping) ----
+__global__ void k_arena_init(ArenaState *st, uint32_t slots)
+{
+    st->top = 0; st->peak = 0; st->nslots = 0; st->failed = 0; st->slots_cap = slots; st->pad = 0;
+    for (uint32_t k = 0; k < slots; ++k) { st->slot[k].offset = 0; st->slot[k].size = 0; }
+}
+
+// After the kernels of a push: the container is complete, record it and move the top past it.
+__global__ void k_arena_pushed(BatchC b, ArenaState *st, uint32_t slot)
+{
+    const TensorMeta &tm = b.tmeta[0];
+    if (slot >= st->slots_cap) { st->failed += 1; return; }
+    if (tm.skip) {                                   // it did not fit: the slot stays empty
+        st->slot[slot].offset = st->top; st->slot[slot].size = 0;
+        st->failed += 1;
+    } else {
+        st->slot[slot].offset = st->top; st->slot[slot].size = tm.total_size;
+        st->top += (tm.total_size + kArenaAlign - 1) / kArenaAlign * kArenaAlign;
+        if (st->top > st->peak) st->peak = st->top;
+    }
+    if (slot + 1 > st->nslots) st->nslots = slot + 1;
+}
+
+// A container is no longer needed.  Space comes back when the slots above it are free too.
+__global__ void k_arena_release(ArenaState *st, uint32_t slot)
+{
+    if (slot >= st->slots_cap) return;
+    st->slot[slot].size = 0;
+    uint32_t n = st->nslots;
+    while (n > 0 && st->slot[n - 1].size == 0) { --n; st->top = st->slot[n].offset; }
+    st->nslots = n;
+}
+
 }  // namespace
+
+void launch_arena_init(ArenaState *st_dev, uint32_t slots, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_arena_init, dim3(1), dim3(1), 0, st, st_dev, slots);
+}
+void launch_arena_pushed(const BatchC &b, ArenaState *st_dev, uint32_t slot, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_arena_pushed, dim3(1), dim3(1), 0, st, b, st_dev, slot);
+}
+void launch_arena_release(ArenaState *st_dev, uint32_t slot, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_arena_release, dim3(1), dim3(1), 0, st, st_dev, slot);
+}
 
 void launch_widen(uint16_t *sym, uint32_t *wide, uint32_t sym_off, uint32_t nchunks, hipStream_t st)
 {
