@@ -39,7 +39,7 @@ def build(force: bool = False) -> str:
 
 class _Config(C.Structure):
     _fields_ = [("radius", C.c_uint32), ("chunk", C.c_uint32), ("sub", C.c_uint32),
-                ("guard_shift", C.c_uint32)]
+                ("guard_shift", C.c_uint32), ("zero_blocks", C.c_uint32)]
 
 
 class _Stages(C.Structure):
@@ -55,9 +55,10 @@ class Config:
     chunk: int = 4096
     sub: int = 128
     guard_shift: int = 7
+    zero_blocks: int = 0          # 1: sub-blocks of zero residuals are left out of the bit stream (version 2)
 
     def c(self) -> _Config:
-        return _Config(self.radius, self.chunk, self.sub, self.guard_shift)
+        return _Config(self.radius, self.chunk, self.sub, self.guard_shift, self.zero_blocks)
 
 
 _lib = None
@@ -77,6 +78,8 @@ def lib() -> C.CDLL:
         L.orc_histogram.argtypes = [vp, sz, u32, vp]; L.orc_histogram.restype = None
         L.orc_codebook_lengths.argtypes = [vp, u32, vp]; L.orc_codebook_lengths.restype = C.c_int
         L.orc_canonical_codes.argtypes = [vp, u32, vp]; L.orc_canonical_codes.restype = C.c_int
+        L.orc_zero_blocks.argtypes = [vp, sz, u32, u32, vp]; L.orc_zero_blocks.restype = None
+        L.orc_histogram_coded.argtypes = [vp, sz, u32, u32, vp, vp]; L.orc_histogram_coded.restype = None
         L.orc_bound.argtypes = [vp, vp]; L.orc_bound.restype = sz
         L.orc_compress.argtypes = [vp, vp, f32, vp, vp, sz, vp, vp]; L.orc_compress.restype = C.c_int
         L.orc_decompress.argtypes = [vp, sz, vp, f32, vp, vp]; L.orc_decompress.restype = C.c_int
@@ -149,6 +152,22 @@ def histogram(sym: np.ndarray, nsym: int = 1024) -> np.ndarray:
     sym = np.ascontiguousarray(sym, dtype=np.uint16).reshape(-1)
     cnt = np.empty(nsym, dtype=np.uint32)
     lib().orc_histogram(_p(sym), sym.size, nsym, _p(cnt))
+    return cnt
+
+
+def zero_blocks(sym: np.ndarray, radius: int = 512, sub: int = 128) -> np.ndarray:
+    """C4'/C6': one flag per sub-block of the linear symbol array, 1 = nothing but the zero residual."""
+    sym = np.ascontiguousarray(sym, dtype=np.uint16).reshape(-1)
+    flags = np.zeros((sym.size + sub - 1) // sub + 1, dtype=np.uint8)
+    lib().orc_zero_blocks(_p(sym), sym.size, radius, sub, _p(flags))
+    return flags[:(sym.size + sub - 1) // sub]
+
+
+def histogram_coded(sym: np.ndarray, flags: np.ndarray, nsym: int = 1024, sub: int = 128) -> np.ndarray:
+    sym = np.ascontiguousarray(sym, dtype=np.uint16).reshape(-1)
+    flags = np.ascontiguousarray(np.concatenate([flags, [0]]), dtype=np.uint8)
+    cnt = np.empty(nsym, dtype=np.uint32)
+    lib().orc_histogram_coded(_p(sym), sym.size, nsym, sub, _p(flags), _p(cnt))
     return cnt
 
 

@@ -22,7 +22,10 @@
  * Lorenzo/prefix-sum identity and closed forms vs numpy cumsum, histogram vs
  * bincount, RFC 1951 canonical-code example, Kraft equality, brute-force
  * optimal cost on tiny alphabets, independent heap Huffman cost, hand-packed
- * bitstreams, header-corruption rejection, hand-computed 1x1x2x2 container.
+ * bitstreams, header-corruption rejection, hand-computed 1x1x2x2 container;
+ * for the zero-block variant: the flags against their definition, a worked
+ * example, the same symbols and reconstruction as the plain variant, never
+ * more payload bits than the plain variant.
  * The tie-break among equally optimal codebooks (C5) is a convention fixed
  * here: apart from its worked examples it is "parity unpinned".
  *
@@ -46,7 +49,8 @@
 
 #define ORC_QMAX        16384
 #define ORC_HEADER      256
-#define ORC_VERSION     1
+#define ORC_VERSION     1   /* every code is in the bit stream                                   */
+#define ORC_VERSION_ZB  2   /* sub-blocks of zero residuals are left out of it (C4', C6' below)  */
 #define ORC_MAX_RADIUS  512
 #define ORC_MAX_NSYM    (2 * ORC_MAX_RADIUS)
 
@@ -55,6 +59,7 @@ typedef struct {
     uint32_t chunk;        /* codes per Huffman chunk                            */
     uint32_t sub;          /* codes per sub-block (divides chunk)                */
     uint32_t guard_shift;  /* eb_in = eb - eb * 2^-guard_shift                   */
+    uint32_t zero_blocks;  /* 1: leave sub-blocks of zero residuals out (version 2) */
 } orc_config;
 
 /* Optional stage dumps; any pointer may be NULL.  Buffers are caller-owned and
@@ -198,6 +203,36 @@ void orc_histogram(const uint16_t *sym, size_t n, uint32_t nsym, uint32_t *cnt)
     for (size_t i = 0; i < n; ++i) cnt[sym[i]] += 1;
 }
 
+/* ------------------------------------------------------------ C4', C6' ---- */
+/* The sparsity-aware front end (format version 2).  Activation data are
+ * dominated by zeros (Section 3.2 treats them apart: they carry no error;
+ * Section 4.4 restores them exactly): where a whole sub-block of `sub`
+ * consecutive codes holds nothing but the zero residual (symbol R), that fact
+ * alone is recorded -- the sub-block's stored bit count is 0, a value no coded
+ * sub-block can have, since every codeword has at least one bit -- and its
+ * codes take no part in the histogram, the codebook or the bit stream.
+ * flags[j] = 1 for every such sub-block j (sub-blocks tile the linear NCHW
+ * array from element 0; the last one may be short; one without elements is
+ * never flagged). */
+void orc_zero_blocks(const uint16_t *sym, size_t n, uint32_t radius, uint32_t sub, uint8_t *flags)
+{
+    size_t nblocks = (n + sub - 1) / sub;
+    for (size_t j = 0; j < nblocks; ++j) {
+        size_t a = j * sub, b = a + sub < n ? a + sub : n;
+        uint8_t all_zero = 1;
+        for (size_t i = a; i < b; ++i) if (sym[i] != radius) all_zero = 0;
+        flags[j] = all_zero;
+    }
+}
+
+/* C4 restricted to the codes that are coded: those outside flagged sub-blocks. */
+void orc_histogram_coded(const uint16_t *sym, size_t n, uint32_t nsym, uint32_t sub, const uint8_t *flags,
+                         uint32_t *cnt)
+{
+    for (uint32_t k = 0; k < nsym; ++k) cnt[k] = 0;
+    for (size_t i = 0; i < n; ++i) if (!flags[i / sub]) cnt[sym[i]] += 1;
+}
+
 /* ------------------------------------------------------------------ C5 ---- */
 /* Huffman code lengths by the two-queue construction, with the tie-break fixed:
  * leaves sorted ascending by (count, symbol); on equal weight a leaf is taken
@@ -312,6 +347,7 @@ static int check_config(const orc_config *cfg)
     if (cfg->sub < 1 || cfg->sub > 1024) return ORC_E_ARG;
     if (cfg->chunk < cfg->sub || cfg->chunk % cfg->sub != 0 || cfg->chunk > (1u << 20)) return ORC_E_ARG;
     if (cfg->guard_shift < 1 || cfg->guard_shift > 23) return ORC_E_ARG;
+    if (cfg->zero_blocks > 1) return ORC_E_ARG;
     return ORC_OK;
 }
 
@@ -403,16 +439,22 @@ int orc_compress(const float *x, const int64_t shape[4], float eb, const orc_con
     uint16_t *sym = (uint16_t *)malloc(sizeof(uint16_t) * (n + 1));
     uint32_t *oidx = (uint32_t *)malloc(sizeof(uint32_t) * (n + 1));
     int32_t *oval = (int32_t *)malloc(sizeof(int32_t) * (n + 1));
+    uint8_t *zflag = (uint8_t *)calloc(n / cfg->sub + 2, 1);   /* all 0 unless cfg->zero_blocks */
     uint32_t cnt[ORC_MAX_NSYM];
     uint8_t lens[ORC_MAX_NSYM];
     uint64_t codes[ORC_MAX_NSYM];
-    if (!q || !delta || !sym || !oidx || !oval) { rc = ORC_E_NOMEM; goto done; }
+    if (!q || !delta || !sym || !oidx || !oval || !zflag) { rc = ORC_E_NOMEM; goto done; }
 
     /* C1..C5 */
     uint64_t range_events = orc_prequant(x, n, r, q);
     orc_lorenzo2d(q, planes, H, W, delta);
     uint64_t n_out = orc_split(delta, n, R, sym, oidx, oval);
-    orc_histogram(sym, n, nsym, cnt);
+    if (cfg->zero_blocks) {
+        orc_zero_blocks(sym, n, R, cfg->sub, zflag);
+        orc_histogram_coded(sym, n, nsym, cfg->sub, zflag, cnt);
+    } else {
+        orc_histogram(sym, n, nsym, cnt);
+    }
     int max_len = orc_codebook_lengths(cnt, nsym, lens);
     if (max_len < 0) { rc = max_len; goto done; }
     if ((rc = orc_canonical_codes(lens, nsym, codes)) != ORC_OK) goto done;
@@ -426,7 +468,7 @@ int orc_compress(const float *x, const int64_t shape[4], float eb, const orc_con
     for (uint32_t c = 0; c < nchunks; ++c) {
         size_t lo = (size_t)c * cfg->chunk, hi = lo + cfg->chunk < n ? lo + cfg->chunk : n;
         uint64_t bits = 0;
-        for (size_t i = lo; i < hi; ++i) bits += lens[sym[i]];
+        for (size_t i = lo; i < hi; ++i) if (!zflag[i / cfg->sub]) bits += lens[sym[i]];
         total_bits += bits;
         payload_units += (bits + 127) / 128;
     }
@@ -454,7 +496,7 @@ int orc_compress(const float *x, const int64_t shape[4], float eb, const orc_con
     /* C7: write the container; everything not written below stays zero */
     memset(out, 0, total);
     memcpy(out + H_MAGIC, "CMPZ", 4);
-    put_u32(out + H_VERSION, ORC_VERSION);
+    put_u32(out + H_VERSION, cfg->zero_blocks ? ORC_VERSION_ZB : ORC_VERSION);
     put_u32(out + H_STATUS, 0);
     { uint32_t ebits; memcpy(&ebits, &eb, 4); put_u32(out + H_EB_BITS, ebits); }
     for (int i = 0; i < 4; ++i) put_u32(out + H_SHAPE + 4 * i, (uint32_t)shape[i]);
@@ -494,7 +536,8 @@ int orc_compress(const float *x, const int64_t shape[4], float eb, const orc_con
                 if (a > hi) a = hi;
                 if (b > hi) b = hi;
                 uint64_t before = pos;
-                for (size_t i = a; i < b; ++i) put_bits(stream, &pos, codes[sym[i]], lens[sym[i]]);
+                for (size_t i = a; i < b; ++i)
+                    if (!zflag[i / cfg->sub]) put_bits(stream, &pos, codes[sym[i]], lens[sym[i]]);
                 put_u16(out + off_sub_bits + 2 * ((size_t)c * nsub + j), (uint16_t)(pos - before));
             }
             unit += (pos + 127) / 128;
@@ -509,7 +552,7 @@ int orc_compress(const float *x, const int64_t shape[4], float eb, const orc_con
     rc = range_events ? ORC_W_RANGE : ORC_OK;
 
 done:
-    free(q); free(delta); free(sym); free(oidx); free(oval);
+    free(q); free(delta); free(sym); free(oidx); free(oval); free(zflag);
     return rc;
 }
 
@@ -563,6 +606,10 @@ static int decode_symbols(const uint8_t *buf, size_t n, const orc_config *cfg, u
             if (b > hi) b = hi;
             uint64_t sb = get_u16(buf + off_sub_bits + 2 * ((size_t)c * nsub + j));
             if (start + sb > chunk_bits) return ORC_E_FORMAT;
+            if (cfg->zero_blocks && sb == 0 && a < b) {       /* C6': nothing but zero residuals */
+                for (size_t i = a; i < b; ++i) sym[i] = (uint16_t)cfg->radius;
+                continue;
+            }
             uint64_t pos = start;
             for (size_t i = a; i < b; ++i) {
                 uint64_t code = 0;
@@ -602,14 +649,15 @@ int orc_decompress(const uint8_t *buf, size_t size, const int64_t shape[4], floa
     /* header: format first, then agreement with the caller's arguments */
     if (size < ORC_HEADER) return ORC_E_FORMAT;
     if (memcmp(buf + H_MAGIC, "CMPZ", 4) != 0) return ORC_E_FORMAT;
-    if (get_u32(buf + H_VERSION) != ORC_VERSION) return ORC_E_FORMAT;
+    if (get_u32(buf + H_VERSION) != ORC_VERSION && get_u32(buf + H_VERSION) != ORC_VERSION_ZB) return ORC_E_FORMAT;
     if (get_u32(buf + H_STATUS) != 0) return ORC_E_FORMAT;
     for (size_t i = H_TOTAL_SIZE + 8; i < ORC_HEADER; ++i) if (buf[i] != 0) return ORC_E_FORMAT;
     { uint32_t ebits; memcpy(&ebits, &eb, 4); if (get_u32(buf + H_EB_BITS) != ebits) return ORC_E_MISMATCH; }
     for (int i = 0; i < 4; ++i)
         if (get_u32(buf + H_SHAPE + 4 * i) != (uint32_t)shape[i]) return ORC_E_MISMATCH;
     if (get_u32(buf + H_RADIUS) != cfg->radius || get_u32(buf + H_CHUNK) != cfg->chunk ||
-        get_u32(buf + H_SUB) != cfg->sub || get_u32(buf + H_GUARD) != cfg->guard_shift)
+        get_u32(buf + H_SUB) != cfg->sub || get_u32(buf + H_GUARD) != cfg->guard_shift ||
+        get_u32(buf + H_VERSION) != (cfg->zero_blocks ? ORC_VERSION_ZB : ORC_VERSION))
         return ORC_E_MISMATCH;
     if (get_u64(buf + H_NUMEL) != numel) return ORC_E_FORMAT;
 
@@ -652,7 +700,8 @@ int orc_decompress(const uint8_t *buf, size_t size, const int64_t shape[4], floa
         }
         if (used >= 2 && kraft != one) return ORC_E_FORMAT;
         if (used == 1 && mx != 1) return ORC_E_FORMAT;
-        if (used == 0 && numel != 0) return ORC_E_FORMAT;
+        /* no codeword at all: an empty tensor, or (version 2) nothing but flagged sub-blocks */
+        if (used == 0 && numel != 0 && !(cfg->zero_blocks && get_u64(buf + H_TOTAL_BITS) == 0)) return ORC_E_FORMAT;
         if (get_u32(buf + H_MAXLEN) != mx) return ORC_E_FORMAT;
         for (size_t i = off_lens + nsym; i < off_chunk_off; ++i) if (buf[i] != 0) return ORC_E_FORMAT;
     }
