@@ -36,7 +36,7 @@
  * so that |x - x'| <= eb for every element whose |x * r| <= 16384.
  *
  * Container (little-endian; every section 16-byte aligned; padding bytes zero):
- *    header, 256 bytes: +0 "CMPZ", +4 version u32 (1), +8 status u32 (0 = complete,
+ *    header, 256 bytes: +0 "CMPZ", +4 version u32 (1; 2 with CMP_F_ZERO_BLOCKS), +8 status u32 (0 = complete,
  *      2 = did not fit), +12 eb bits u32, +16 shape u32[4], +32 numel u64,
  *      +40 radius, +44 chunk, +48 sub, +52 guard_shift, +56 nchunks, +60 n_outliers,
  *      +64 range_events, +68 max_len (all u32), +72 total_bits u64, then u64 offsets of
@@ -47,7 +47,8 @@
  *                                    read most significant bit first
  *    chunk_off u32[nchunks+1]        start of each chunk's bit stream in 16-byte units
  *    outl_off  u32[nchunks+1]        number of outliers before each chunk
- *    sub_bits  u16[nchunks*chunk/sub] bits of every sub-block of `sub` consecutive codes
+ *    sub_bits  u16[nchunks*chunk/sub] bits of every sub-block of `sub` consecutive codes (version 2:
+ *                                    0 for a sub-block of zero residuals, which has no bits in the payload)
  *    payload   chunk bit streams, each padded with zero bits to a multiple of 128 bits;
  *              bit k of a stream is bit 31-(k%32) of little-endian 32-bit word k/32
  *    outl_idx  u32[n_outliers]       linear NCHW index, ascending
@@ -83,9 +84,18 @@ typedef struct {
     uint32_t guard_shift;  /* 1..23, see "Arithmetic" above                                    */
     uint64_t max_numel;    /* most elements one launch group holds: no tensor may be larger, and a
                               batch with more in total is worked off in several groups         */
+    uint32_t flags;        /* CMP_F_* below                                                    */
+    uint32_t reserved;     /* 0                                                                */
 } cmp_config;
 
-/* Defaults: radius 512, chunk 4096, sub 128, guard_shift 7, max_numel 2^28. */
+/* Sparsity-aware front end (container version 2).  Activation data are dominated by zeros
+ * (Section 3.2; Section 4.4 restores them exactly): a sub-block whose residuals are all zero is
+ * recorded by a stored bit count of 0 -- a value no coded sub-block can have -- and its codes take
+ * no part in the histogram, the codebook or the bit stream.  Compress and decompress must agree
+ * on the flag (CMP_E_MISMATCH otherwise). */
+#define CMP_F_ZERO_BLOCKS 1u
+
+/* Defaults: radius 512, chunk 4096, sub 128, guard_shift 7, max_numel 2^28, flags 0. */
 void cmp_default_config(cmp_config *cfg);
 
 /* Create a context on GPU `device` and allocate its scratch (about

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libcmpz.so")
 CMP_OK, CMP_E_ARG, CMP_E_NOSPACE, CMP_E_FORMAT, CMP_E_MISMATCH, CMP_E_HIP, CMP_W_RANGE = 0, -1, -2, -3, -4, -5, 1
 CMP_STAGE_QUANT_CODES, CMP_STAGE_HIST, CMP_STAGE_LENS, CMP_STAGE_CODES = 0, 1, 2, 3
 CMP_STAGE_OUTLIER_IDX, CMP_STAGE_OUTLIER_VAL = 4, 5
+CMP_F_ZERO_BLOCKS = 1
 
 EXPORTS = ["cmp_default_config", "cmp_create", "cmp_destroy", "cmp_bound", "cmp_compress",
            "cmp_compressed_size", "cmp_decompress", "cmp_last_status", "cmp_debug_stage", "cmp_strerror",
@@ -33,7 +34,8 @@ class cmp_controller_config(C.Structure):
 
 class cmp_config(C.Structure):
     _fields_ = [("radius", C.c_uint32), ("chunk", C.c_uint32), ("sub", C.c_uint32),
-                ("guard_shift", C.c_uint32), ("max_numel", C.c_uint64)]
+                ("guard_shift", C.c_uint32), ("max_numel", C.c_uint64), ("flags", C.c_uint32),
+                ("reserved", C.c_uint32)]
 
 
 _lib = None
@@ -261,8 +263,8 @@ class CmpError(RuntimeError):
 class Context:
     """Owns one cmp_ctx.  Tensors supply device memory; the current torch stream is used."""
 
-    def __init__(self, radius=512, chunk=4096, sub=128, guard_shift=7, max_numel=1 << 28, device=0):
-        cfg = cmp_config(radius, chunk, sub, guard_shift, max_numel)
+    def __init__(self, radius=512, chunk=4096, sub=128, guard_shift=7, max_numel=1 << 28, device=0, zero_blocks=0):
+        cfg = cmp_config(radius, chunk, sub, guard_shift, max_numel, CMP_F_ZERO_BLOCKS if zero_blocks else 0, 0)
         rc, self._h = cmp_create(cfg, device)
         if rc != CMP_OK:
             self._h = None

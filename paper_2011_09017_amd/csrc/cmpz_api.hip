@@ -58,6 +58,7 @@ bool config_ok(const cmp_config &c)
     if (c.sub != 32 && c.sub != 64 && c.sub != 128) return false;
     if (c.guard_shift < 1 || c.guard_shift > 23) return false;
     if (c.max_numel > kMaxNumel) return false;
+    if ((c.flags & ~CMP_F_ZERO_BLOCKS) || c.reserved) return false;
     return true;
 }
 
@@ -153,6 +154,7 @@ void cmp_default_config(cmp_config *cfg)
     if (!cfg) return;
     cfg->radius = 512; cfg->chunk = kChunk; cfg->sub = 128; cfg->guard_shift = 7;
     cfg->max_numel = 1ull << 28;
+    cfg->flags = 0; cfg->reserved = 0;
 }
 
 int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device)
@@ -245,6 +247,7 @@ void group_begin(BatchC *b, const cmp_config &cfg, const Scratch &s)
 {
     std::memset(b, 0, sizeof(*b));
     b->radius = cfg.radius; b->sub = cfg.sub; b->guard_shift = cfg.guard_shift;
+    b->zero_blocks = (cfg.flags & CMP_F_ZERO_BLOCKS) ? 1u : 0u;
     b->sym = s.sym; b->hist = s.hist; b->hist_copy = s.hist_copy; b->lens = s.lens; b->codes = s.codes;
     b->enc32 = s.enc32; b->outl_cnt = s.outl_cnt; b->wide = s.wide; b->chunk_bits = s.chunk_bits;
     b->sym_off = cfg.radius > 128 ? cfg.radius - 128 : 0;
@@ -486,6 +489,7 @@ int cmp_arena_pop(cmp_ctx *ctx, const void *d_arena, void *d_state, uint32_t slo
     std::memset(&b, 0, sizeof(b));
     b.n = 1;
     b.radius = ctx->cfg.radius; b.sub = ctx->cfg.sub; b.guard_shift = ctx->cfg.guard_shift;
+    b.zero_blocks = (ctx->cfg.flags & CMP_F_ZERO_BLOCKS) ? 1u : 0u;
     b.meta = ctx->s.meta; b.status = ctx->s.status;
     TensorD &t = b.t[0];
     t.buf = static_cast<const uint8_t *>(d_arena);
@@ -582,7 +586,7 @@ int cmp_compressed_size(cmp_ctx *ctx, const void *d_buf, size_t *h_size, void *s
     Header hd;
     if (hipMemcpyAsync(&hd, d_buf, sizeof(hd), hipMemcpyDeviceToHost, st) != hipSuccess) return CMP_E_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return CMP_E_HIP;
-    if (hd.magic != kMagic || hd.version != kVersion) return CMP_E_FORMAT;
+    if (hd.magic != kMagic || (hd.version != kVersion && hd.version != kVersionZB)) return CMP_E_FORMAT;
     *h_size = (size_t)hd.total_size;
     if (hd.status != 0) return CMP_E_NOSPACE;
     if (hd.range_events != 0) return CMP_W_RANGE;
@@ -621,6 +625,7 @@ int cmp_decompress_batch(cmp_ctx *ctx, int n, const void *const *d_buf, const si
         BatchD b;
         std::memset(&b, 0, sizeof(b));
         b.radius = ctx->cfg.radius; b.sub = ctx->cfg.sub; b.guard_shift = ctx->cfg.guard_shift;
+        b.zero_blocks = (ctx->cfg.flags & CMP_F_ZERO_BLOCKS) ? 1u : 0u;
         b.meta = ctx->s.meta; b.status = ctx->s.status;
         for (int i = i0; i < n && i < i0 + kBatchMax; ++i) b.t[b.n++] = td[(size_t)i];
         launch_decode_fused(b, &ctx->prof, st);

@@ -89,8 +89,24 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist(BatchC b,
         const bool all_mode = (s[0] == (uint32_t)R) && (s[1] == (uint32_t)R) &&
                               (s[2] == (uint32_t)R) && (s[3] == (uint32_t)R);
         const unsigned long long m = __ballot(all_mode);
-        if (all_mode) {
-            if ((int)(__lane_id()) == __ffsll((long long)m) - 1) atomicAdd(&hist[R], 4u * (uint32_t)__popcll(m));
+        // Version 2: the zero residuals of a sub-block that holds nothing else are not counted.  A
+        // sub-block is sub/4 neighbouring lanes; lanes past the end of the tensor are not here and
+        // count as empty.
+        bool counted = true;
+        if (b.zero_blocks) {
+            bool az = true;
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) az = az && (s[j] == (uint32_t)R || s[j] == 0xffffffffu);
+            const unsigned long long zm = __ballot(az) | ~__ballot(true);
+            const uint32_t g = b.sub / 4u, ln = (uint32_t)__lane_id();
+            const unsigned long long grp = ((1ull << g) - 1ull) << (ln & ~(g - 1u));
+            counted = (zm & grp) != grp;
+        }
+        if (!counted) {
+            // nothing to count
+        } else if (all_mode) {
+            if (b.zero_blocks) atomicAdd(&hist[R], 4u);          // (the lanes counted together may not all be counted)
+            else if ((int)(__lane_id()) == __ffsll((long long)m) - 1) atomicAdd(&hist[R], 4u * (uint32_t)__popcll(m));
         } else {
             uint32_t run = 1;
 #pragma unroll

@@ -99,9 +99,10 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
     if (tid == 0) {
         uint32_t bad = 0;
         const Layout &l = a.lay;
-        if (hd->magic != kMagic || hd->version != kVersion || hd->status != 0) bad = kStFormat;
+        if (hd->magic != kMagic || (hd->version != kVersion && hd->version != kVersionZB) || hd->status != 0) bad = kStFormat;
         if (!bad) {
             if (hd->eb_bits != a.eb_bits) bad = kStMismatch;
+            if (hd->version != (a.zero_blocks ? kVersionZB : kVersion)) bad = kStMismatch;
             for (int k = 0; k < 4; ++k) if (hd->shape[k] != a.shape[k]) bad = kStMismatch;
             if (hd->radius != a.radius || hd->chunk != kChunk || hd->sub != a.sub ||
                 hd->guard_shift != a.guard_shift) bad = kStMismatch;
@@ -177,7 +178,8 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
             const uint64_t one = 1ull << kMaxCodeLen;
             if (used >= 2 && incl != one) bad = kStFormat;
             if (used == 1 && max_len != 1) bad = kStFormat;
-            if (used == 0 && a.numel != 0) bad = kStFormat;
+            // no codeword at all: an empty tensor, or (version 2) nothing but sub-blocks of zero residuals
+            if (used == 0 && a.numel != 0 && !(a.zero_blocks && hd->total_bits == 0)) bad = kStFormat;
             if (hd->max_len != max_len) bad = kStFormat;
             if (bad) *bad2_s = bad;
             T.max_len = max_len;

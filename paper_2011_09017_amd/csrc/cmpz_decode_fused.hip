@@ -288,8 +288,10 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
             const uint32_t uu0 = fa.uu0, uu1 = fa.uu1;
             bool lbad = !(uu0 <= uu1 && uu1 <= payload_units);
             const uint32_t nw = lbad ? 0u : (uu1 - uu0) * 4;
-            // a sub-block holds at least one codeword of at least one bit: an empty chunk stream is damage
-            if (nw == 0 || (uint64_t)start + sbits > (uint64_t)nw * 32) lbad = true;
+            // version 2: a stored bit count of 0 stands for a sub-block of zero residuals
+            const bool zeros_only = a.zero_blocks && sbits == 0;
+            // otherwise a sub-block holds at least one codeword of at least one bit: an empty chunk stream is damage
+            if ((nw == 0 && !zeros_only) || (uint64_t)start + sbits > (uint64_t)nw * 32) lbad = true;
             const uint32_t el0 = g << kLog;              // first element of the sub-block
             const uint32_t n_here = (a.numel - el0 >= (uint32_t)SUB) ? (uint32_t)SUB : a.numel - el0;
             // elements of this sub-block that belong to the band: k in [klo, khi)
@@ -316,6 +318,10 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
                 const uint32_t *__restrict__ gw =
                     reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_payload + (uint64_t)uu0 * 16);
                 auto run_decode = [&](uint32_t count, uint32_t skip, auto put) -> uint32_t {
+                    if (zeros_only) {
+                        for (uint32_t k = skip; k < count; ++k) put(k, 0);
+                        return start;
+                    }
                     if (staged)
                         return decode_lds(T, S, spos, count, skip, put, lbad) - spos + start;
                     return decode_run<false>(T, [&](uint32_t k) -> uint32_t { return gw[k < last ? k : last]; }, start,

@@ -75,7 +75,11 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecompressArgs a, const 
         if ((uint64_t)start + sb > (uint64_t)nwords * 32) { bad = true; nwords = 0; }
         int16_t *my = stage + tid * kStride;
         uint32_t end = 0;
-        if (nwords) {
+        if (a.zero_blocks && sb == 0 && !bad) {
+            // version 2: a stored bit count of 0 stands for a sub-block of zero residuals
+            for (uint32_t k = 0; k < n_here; ++k) my[k] = 0;
+            end = start;
+        } else if (nwords) {
             const uint32_t last = nwords - 1;
             end = decode_run<false>(T, [&](uint32_t k) -> uint32_t { return words[k < last ? k : last]; }, start, n_here, 0u,
                              [&](uint32_t k, int32_t d) { my[k] = (int16_t)d; }, bad);

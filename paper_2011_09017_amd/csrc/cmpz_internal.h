@@ -18,7 +18,8 @@ constexpr uint32_t kHeaderBytes = 256;
 // last element before they compare, so the bound stays two such steps below 2^32.
 constexpr uint64_t kMaxNumel    = (1ull << 32) - 8192;
 constexpr uint32_t kMaxCodeLen  = 48;       // counts below 2^32 bound a Huffman depth by 45
-constexpr uint32_t kVersion     = 1;
+constexpr uint32_t kVersion     = 1;        // every code is in the bit stream
+constexpr uint32_t kVersionZB   = 2;        // sub-blocks of zero residuals are left out of it
 constexpr uint32_t kHistCopies  = 8;        // global histogram replicas that workgroups flush into (less contention)
 
 // Container header, little-endian, 256 bytes; bytes 144..255 are zero.
@@ -156,6 +157,7 @@ __device__ __forceinline__ OutRef resolve_out(const TensorC &tc)
 struct BatchC {
     uint32_t n;                 // tensors of this launch group
     uint32_t radius, sub, guard_shift;
+    uint32_t zero_blocks;       // 1: sub-blocks of zero residuals are not coded (container version 2)
     uint32_t sweep_chunks;      // chunks per workgroup in the first sweep
     uint32_t sweep_wgs, pack_wgs, total_chunks;
     // context scratch
@@ -186,6 +188,7 @@ struct DecompressArgs {
     uint32_t       numel, planes, H, W, HW;
     uint32_t       shape[4];
     uint32_t       radius, sub, guard_shift, eb_bits;
+    uint32_t       zero_blocks;
     float          s;
     Layout         lay;
     uint32_t *meta;
@@ -210,7 +213,7 @@ struct TensorD {
 
 struct BatchD {
     uint32_t  n;
-    uint32_t  radius, sub, guard_shift;
+    uint32_t  radius, sub, guard_shift, zero_blocks;
     uint32_t *meta;
     uint32_t *status;
     TensorD   t[kBatchMax];
@@ -227,6 +230,7 @@ __host__ __device__ inline DecompressArgs decompress_args(const BatchD &b, const
     a.H = t.shape[2]; a.W = t.shape[3]; a.HW = a.H * a.W;
     for (int i = 0; i < 4; ++i) a.shape[i] = t.shape[i];
     a.radius = b.radius; a.sub = b.sub; a.guard_shift = b.guard_shift; a.eb_bits = t.eb_bits;
+    a.zero_blocks = b.zero_blocks;
     a.s = t.s;
     a.lay = make_layout(t.numel, b.radius, b.sub);
     a.meta = b.meta; a.status = b.status;
@@ -259,6 +263,14 @@ __device__ __forceinline__ int delta_from_x(const float *__restrict__ x, uint32_
     const int up = (h > 0) ? quant(x[i - W], r) : 0;
     const int diag = (h > 0 && w > 0) ? quant(x[i - W - 1], r) : 0;
     return q - left - up + diag;
+}
+
+// True in every lane of an aligned group of g lanes (g a power of two) iff `flag` holds in all of them.
+__device__ __forceinline__ bool group_all(bool flag, uint32_t lane, uint32_t g)
+{
+    const unsigned long long m = __ballot(flag);
+    const unsigned long long grp = (g >= 64u ? ~0ull : ((1ull << g) - 1ull)) << (lane & ~(g - 1u));
+    return (m & grp) == grp;
 }
 
 // --- wave-level scans on the DPP network (row shifts inside 16-lane rows, then the two

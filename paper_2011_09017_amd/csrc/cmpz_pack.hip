@@ -54,6 +54,8 @@ __device__ __forceinline__ void unpack8(const uint4 &v, uint32_t s[8])
 // or 16 consecutive bytes (one 128-bit load, consecutive lanes consecutive addresses), so a
 // sub-block of 32, 64 or 128 codes is a few neighbouring lanes of one DPP row.
 // ---------------------------------------------------------------------------
+// ZB: container version 2 (sub-blocks of zero residuals have no bits)
+template <bool ZB>
 __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
 {
     __shared__ uint32_t lens_s[kMaxSym / 4 + 1];     // code length per symbol, one byte each; symbol kPastEnd: 0
@@ -126,18 +128,28 @@ __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
                     uint32_t bits = 0;
 #pragma unroll
                     for (int k = 0; k < 8; ++k) bits += L[s[k]];
+                    if (ZB) {
+                        bool az = true;          // nothing but the zero residual (or nothing at all) in this lane
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) az = az && (s[k] == b.radius || s[k] == kPastEnd);
+                        if (group_all(az, (uint32_t)lane, b.sub / 8)) bits = 0;
+                    }
                     emit(bits, (1024u * qt + 512u * j) / b.sub, b.sub / 8);
                 }
             } else {
                 const uint32_t w[4] = {v[qt][0].x, v[qt][0].y, v[qt][0].z, v[qt][0].w};
                 const uint32_t i0 = e0 + 1024u * qt + (uint32_t)lane * 16u;
                 uint32_t bits = 0;
+                bool az = true;
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
                     const uint32_t byte = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
                     const uint32_t len = Lo[byte];
-                    bits += (full || i0 + k < numel) ? len : 0u;
+                    const bool there = full || i0 + k < numel;
+                    bits += there ? len : 0u;
+                    az = az && (!there || byte + b.sym_off == b.radius);
                 }
+                if (ZB && group_all(az, (uint32_t)lane, b.sub / 16)) bits = 0;
                 emit(bits, (1024u * qt) / b.sub, b.sub / 16);
             }
         }
@@ -236,7 +248,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(BatchC b)
     Header hd;
     uint32_t *raw = reinterpret_cast<uint32_t *>(&hd);
     for (uint32_t k = 0; k < kHeaderBytes / 4; ++k) raw[k] = 0;
-    hd.magic = kMagic; hd.version = kVersion; hd.status = fits ? 0u : kStNoSpace;
+    hd.magic = kMagic; hd.version = b.zero_blocks ? kVersionZB : kVersion; hd.status = fits ? 0u : kStNoSpace;
     hd.eb_bits = tc.eb_bits;
     for (int k = 0; k < 4; ++k) hd.shape[k] = tc.shape[k];
     hd.numel = tc.numel;
@@ -275,6 +287,7 @@ static_assert(512 * kMaxCodeLen <= kStepBitsMax, "image size");
 constexpr uint32_t kImageUnits = kStepBitsMax / 128 + 2;               // the open unit in front, one of slack behind
 constexpr uint32_t kImageWords = kImageUnits * 4;
 
+template <bool ZB>
 __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
 {
     __shared__ uint64_t table[kMaxSym + 1];          // length << 56 | code; or, as 32-bit words, code << (32 - length) | length
@@ -367,11 +380,18 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
                 }
                 orank += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
             }
+            // version 2: a sub-block of zero residuals (n symbols per lane: sub / n lanes) has no bits
+            bool coded = true;
+            if (ZB) {
+                bool az = true;
+                _Pragma("unroll") for (int k = 0; k < n; ++k) az = az && (s[k] == b.radius || s[k] == kPastEnd);
+                coded = !group_all(az, (uint32_t)lane, b.sub / (uint32_t)n);
+            }
             // bit offsets of the lanes; in the short-code case the table entries stay in registers for the packing
             uint32_t bits = 0;
             uint32_t e[n];
-            if (short_codes) { _Pragma("unroll") for (int k = 0; k < n; ++k) { e[k] = table32[s[k]]; bits += e[k] & 31u; } }
-            else             { _Pragma("unroll") for (int k = 0; k < n; ++k) bits += (uint32_t)(table[s[k]] >> 56); }
+            if (short_codes) { _Pragma("unroll") for (int k = 0; k < n; ++k) { e[k] = coded ? table32[s[k]] : 0u; bits += e[k] & 31u; } }
+            else             { _Pragma("unroll") for (int k = 0; k < n; ++k) bits += coded ? (uint32_t)(table[s[k]] >> 56) : 0u; }
             const uint32_t inc = wave_inclusive_sum(bits);
             uint32_t pos = bitpos - ubase * 128u + inc - bits;        // bit position in the image
             if (short_codes) {
@@ -390,7 +410,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
                 }
             } else {
                 _Pragma("unroll") for (int k = 0; k < n; ++k) {
-                    const uint64_t cw = table[s[k]];
+                    const uint64_t cw = coded ? table[s[k]] : 0ull;
                     const uint32_t len = (uint32_t)(cw >> 56);
                     if (len) {
                         const uint64_t place = (cw & 0x00ffffffffffffffull) << (64u - len);   // left-aligned in 64 bits
@@ -582,9 +602,15 @@ void launch_clear(const BatchC &b, Profiler *prof, hipStream_t st)
 // Bit counts, offsets and header, packing: three launches over all tensors of the group.
 void launch_pack(const BatchC &b, Profiler *prof, hipStream_t st)
 {
-    if (b.pack_wgs) launch(prof, kKLengths, k_lengths, dim3(b.pack_wgs), dim3(kThreads), st, b);
+    if (b.pack_wgs) {
+        if (b.zero_blocks) launch(prof, kKLengths, k_lengths<true>, dim3(b.pack_wgs), dim3(kThreads), st, b);
+        else launch(prof, kKLengths, k_lengths<false>, dim3(b.pack_wgs), dim3(kThreads), st, b);
+    }
     launch(prof, kKScan, k_scan, dim3(b.n), dim3(kScanThreads), st, b);
-    if (b.pack_wgs) launch(prof, kKPack, k_pack, dim3(b.pack_wgs), dim3(kThreads), st, b);
+    if (b.pack_wgs) {
+        if (b.zero_blocks) launch(prof, kKPack, k_pack<true>, dim3(b.pack_wgs), dim3(kThreads), st, b);
+        else launch(prof, kKPack, k_pack<false>, dim3(b.pack_wgs), dim3(kThreads), st, b);
+    }
 }
 
 }  // namespace cmpz

@@ -100,6 +100,7 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
         uint32_t s[16];
         uint32_t nout = 0;
         uint32_t bytes_or = 0;                                       // OR of symbol - sym_off over the thread's elements
+        uint32_t zeros = 0, nhere = 0;                               // zero residuals among the thread's elements; how many it has
         if (g0 < t1) {
             // plane coordinates of the first element, then bit masks over the 16 elements:
             // mw bit j = element j starts a row, mh bit j = element j lies in row 0 of its plane
@@ -136,6 +137,7 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
             for (int k = 0; k < 17; ++k) up[k] = Q[li - (int)W - 1 + k];
 
             const uint32_t nval = (t1 - g0 >= 16u) ? 16u : t1 - g0;
+            nhere = nval;
             if (nval == 16u) {
                 // all 16 elements exist: symbols first, the in-range test on the largest of them
                 uint32_t top = 0;
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
                 }
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
-                    if (s[k] == (uint32_t)R) ++zero_run;
+                    if (s[k] == (uint32_t)R) ++zeros;
                     else atomicAdd(&hist[s[k]], 1u);
                 }
             } else {
@@ -172,12 +174,15 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
                     if ((uint32_t)k < nval) {
                         bytes_or |= in ? sy - b.sym_off : 0x100u;
                         nout += in ? 0u : 1u;
-                        if (s[k] == (uint32_t)R) ++zero_run;
+                        if (s[k] == (uint32_t)R) ++zeros;
                         else atomicAdd(&hist[s[k]], 1u);
                     }
                 }
             }
         }
+        // Version 2: the zero residuals of a sub-block that holds nothing else are not counted (a thread
+        // that found only zeros has touched no other bin).  A sub-block is sub/16 neighbouring threads.
+        if (!(b.zero_blocks && group_all(zeros == nhere, (uint32_t)lane, b.sub / 16u))) zero_run += zeros;
         {
             // the wave's quarter of the chunk: bytes if every symbol has a byte form.  The scratch holds
             // whole chunks: the stores past the end of the tensor stay inside the chunk's slot.

@@ -459,3 +459,55 @@ def test_batch_equals_single_calls_equals_oracle(gpu, orc):
     assert rc == gpu.CMP_E_NOSPACE
     outs4, sizes4, rc = ctx.compress_batch(xs, ebs)                         # and the context is still clean
     assert rc == 0 and sizes4 == sizes and torch.equal(outs4[4][:sizes[4]], outs[4][:sizes[4]])
+
+
+ZB_CASES = [
+    # shape, k, p_zero, eb, sub
+    ((2, 8, 56, 56), 5, 0.85, 1e-2, 32), ((2, 8, 56, 56), 5, 0.85, 1e-2, 64), ((2, 8, 56, 56), 5, 0.85, 1e-2, 128),
+    ((1, 4, 112, 112), 5, 0.5, 1e-2, 32), ((6, 40, 14, 14), 5, 0.85, 1e-2, 32), ((3, 300, 7, 7), 5, 0.85, 1e-2, 32),
+    ((2, 3, 55, 55), 5, 0.85, 1e-3, 64), ((1, 1, 40, 257), 5, 0.85, 1e-2, 32), ((1, 1, 3, 2000), 5, 0.85, 1e-2, 128),
+    ((1, 1, 1, 4099), 5, 0.85, 1e-2, 32), ((1, 2, 300, 300), 5, 0.85, 1e-2, 32),
+]
+
+
+@pytest.mark.parametrize("shape,k,p_zero,eb,sub", ZB_CASES)
+def test_zero_block_variant_bit_exact(gpu, orc, shape, k, p_zero, eb, sub):
+    """Container version 2 (sub-blocks of zero residuals are not coded): every stage, the container and
+    the reconstruction against the oracle's; planes with outliers; a tensor of zeros and a constant one."""
+    ctx = make_ctx(gpu, sub=sub, zero_blocks=1)
+    ocfg = orc.Config(sub=sub, zero_blocks=1)
+    x = activation(shape, k, p_zero, seed=sub + shape[3]).numpy()
+    h = check_case(gpu, orc, x, eb, ctx, ocfg)
+    assert h["version"] == 2
+    x[0, 0, shape[2] // 2, shape[3] // 3] = 25000.0 * eb              # an outlier among the zeros
+    check_case(gpu, orc, x, eb, ctx, ocfg)
+    h = check_case(gpu, orc, np.zeros(shape, np.float32), eb, ctx, ocfg)
+    assert h["total_bits"] == 0 and h["max_len"] == 0
+    check_case(gpu, orc, np.full(shape, 3.25, np.float32), eb, ctx, ocfg)
+    # the two variants do not read each other's containers
+    plain = make_ctx(gpu, sub=sub)
+    buf, size, _ = ctx.compress(torch.from_numpy(x).cuda(), eb)
+    plain.decompress(buf, size, shape, eb)
+    assert plain.last_status() == gpu.CMP_E_MISMATCH
+    buf, size, _ = plain.compress(torch.from_numpy(x).cuda(), eb)
+    ctx.decompress(buf, size, shape, eb)
+    assert ctx.last_status() == gpu.CMP_E_MISMATCH
+
+
+@pytest.mark.parametrize("ti", [0, 13])
+def test_zero_block_variant_config5_sparse_full_size(gpu, orc, ti):
+    wl = WORKLOADS["cfg5_resnet18_stream_sparse"]
+    shape = wl.shapes[ti]
+    ctx = make_ctx(gpu, max_numel=shape[0] * shape[1] * shape[2] * shape[3], sub=32, zero_blocks=1)
+    x = wl.tensor(ti, device="cuda")
+    xh = x.cpu().numpy()
+    ocfg = orc.Config(sub=32, zero_blocks=1)
+    buf, size, rc = ctx.compress(x, 1e-2)
+    assert rc == 0
+    orc_rc, obuf, osize, _ = orc.compress(xh, 1e-2, ocfg)
+    assert orc_rc == 0 and size == osize and np.array_equal(buf[:size].cpu().numpy(), obuf)
+    y = ctx.decompress(buf, size, shape, 1e-2)
+    assert ctx.last_status() == 0
+    orc_rc, oy = orc.decompress(obuf, shape, 1e-2, ocfg)
+    assert orc_rc == 0 and np.array_equal(y.cpu().numpy().view(np.uint32), oy.view(np.uint32))
+    print(f"[parity] version 2 {shape}: ratio {xh.nbytes / size:.3f}", flush=True)
