@@ -18,9 +18,13 @@ Prints ONE JSON line.
                the same leg compares the oracle's containers and reconstructions
                with the GPU's, byte for byte (`parity_checked_tensors`)
 
-Extra keys (context, not the headline): `multi_stream` (the same tensors dealt
-over several streams), `sparse_variant` (the 85 %-zeros variant of the
-workload), `other_configs` (the single-tensor configurations).
+The whole workload is one cmp_compress_batch call and one cmp_decompress_batch
+call per step (--api single: one call per tensor).
+
+Extra keys (context, not the headline): `multi_stream` (single calls dealt over
+several streams), `sparse_variant` (the 85 %-zeros variant of the workload, also
+with the sparsity-aware front end), `other_configs` (the single-tensor
+configurations).
 """
 from __future__ import annotations
 
@@ -57,9 +61,10 @@ MEASURED_TRAFFIC = {
     ("cfg5_resnet18_stream", 32, 1e-2): {
         "profile": "profiles/hbm_traffic_cfg5_resnet18_stream.txt",
         "per_elem": {
-            "k_quant_lorenzo_split_hist": 4.0121 + 2.0323,
-            "k_encode": 2.0330 + 0.7218,
-            "k_decode_fused": 0.8244 + 4.0115,
+            "k_quant_lorenzo_split_hist": 4.0057 + 1.0201,     # 8-bit symbols in the scratch
+            "k_lengths": 1.0089 + 0.0677,
+            "k_pack": 1.0137 + 0.6642,
+            "k_decode_fused": 0.8190 + 4.0024,
         },
     },
 }
@@ -68,7 +73,7 @@ MEASURED_TRAFFIC = {
 class Run:
     """One workload resident on the GPU: inputs, containers, outputs, contexts."""
 
-    def __init__(self, binding, torch, wl, eb, sub, nstreams, dev, api="batch"):
+    def __init__(self, binding, torch, wl, eb, sub, nstreams, dev, api="batch", zero_blocks=0):
         self.b, self.torch, self.wl, self.eb, self.sub = binding, torch, wl, eb, sub
         self.api = api if nstreams == 1 else "single"          # batches are one call on one stream
         self.xs = [wl.tensor(i, device=dev) for i in range(len(wl.shapes))]
@@ -76,9 +81,9 @@ class Run:
         self.total = sum(self.numels)
         S = self.S = max(1, min(nstreams, len(self.xs)))
         if self.api == "batch":
-            self.ctxs = [binding.Context(sub=sub, max_numel=self.total)]
+            self.ctxs = [binding.Context(sub=sub, max_numel=self.total, zero_blocks=zero_blocks)]
         else:
-            self.ctxs = [binding.Context(sub=sub, max_numel=max(self.numels[k::S])) for k in range(S)]
+            self.ctxs = [binding.Context(sub=sub, max_numel=max(self.numels[k::S]), zero_blocks=zero_blocks) for k in range(S)]
         self.bounds = [self.ctxs[0].bound(x.shape) for x in self.xs]
         self.arena = [torch.empty(b, dtype=torch.uint8, device=dev) for b in self.bounds]
         self.outs = [torch.empty_like(x) for x in self.xs]
@@ -356,8 +361,8 @@ def main() -> int:
     run.free()
 
     # ---- extras ------------------------------------------------------------------------
-    def measure(wl2, eb2, nstreams):
-        r = Run(binding, torch, wl2, eb2, args.sub, nstreams, dev, args.api)
+    def measure(wl2, eb2, nstreams, zero_blocks=0):
+        r = Run(binding, torch, wl2, eb2, args.sub, nstreams, dev, args.api, zero_blocks)
         for _ in range(args.warmup):
             r.step()
         r.check()
@@ -374,6 +379,9 @@ def main() -> int:
         sparse = WORKLOADS.get(wl.name + "_sparse")
         if sparse is not None:
             result["sparse_variant"] = dict(measure(sparse, eb, args.streams), workload=sparse.name, p_zero=sparse.p_zero)
+            # the same with the sparsity-aware front end (container version 2)
+            result["sparse_variant_zero_blocks"] = dict(measure(sparse, eb, args.streams, 1), workload=sparse.name,
+                                                        p_zero=sparse.p_zero, container_version=2)
         others = {}
         for name in ("cfg2_vgg16_conv1_2", "cfg3_resnet50_bottleneck", "cfg4_alexnet_conv1"):
             for eb2 in WORKLOADS[name].ebs:
