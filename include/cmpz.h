@@ -95,17 +95,25 @@ typedef struct {
  * on the flag (CMP_E_MISMATCH otherwise). */
 #define CMP_F_ZERO_BLOCKS 1u
 
-/* Defaults: radius 512, chunk 4096, sub 128, guard_shift 7, max_numel 2^28, flags 0. */
+/* Defaults: radius 512, chunk 4096, sub 128, guard_shift 7, max_numel 2^28, flags 0: the
+ * parameters of the compressor stages of Section 3.1 that the paper leaves to the implementation. */
 void cmp_default_config(cmp_config *cfg);
 
-/* Create a context on GPU `device` and allocate its scratch (about
- * 2 bytes * max_numel + 9 bytes per chunk + 1.3 MB of device memory).  cfg == NULL
- * means defaults. */
+/* The framework of Section 4.4 compresses the activation of every convolutional layer in every
+ * iteration: what the kernels need between their stages (Section 3.1: symbols between the two
+ * sweeps, histograms, code tables) is allocated once, here, and reused by every call.
+ * Creates a context on GPU `device` with its scratch (about 2 bytes * max_numel + 9 bytes per chunk
+ * + 1.3 MB of device memory, owned by the context).  cfg == NULL means defaults.  Returns CMP_E_ARG
+ * for an unsupported configuration or device, CMP_E_HIP if the allocation fails (*out = NULL). */
 int cmp_create(cmp_ctx **out, const cmp_config *cfg, int device);
+/* Waits for the device and frees the context's scratch; containers and tensors are the caller's
+ * and are not touched.  NULL is allowed. */
 void cmp_destroy(cmp_ctx *ctx);
 
-/* Worst-case container size in bytes for a tensor of this shape (0 on bad
- * arguments).  A container never exceeds it. */
+/* The compressed activation is held in memory until the backward pass (Section 4.4), in a buffer
+ * the caller sizes before the data are seen: worst-case container size in bytes for a tensor of
+ * this shape (every element an outlier, every code of flat length; 0 on bad arguments).  A
+ * container never exceeds it. */
 size_t cmp_bound(const cmp_ctx *ctx, const int64_t shape[4]);
 
 /* Forward pass (Section 4.4): compress d_x (fp32, shape N,C,H,W) under the
@@ -222,14 +230,18 @@ int cmp_decompress(cmp_ctx *ctx, const void *d_buf, size_t size, const int64_t s
 int cmp_decompress_batch(cmp_ctx *ctx, int n, const void *const *d_buf, const size_t *size, const int64_t (*shapes)[4],
                          const float *eb, float *const *d_xout, void *stream);
 
-/* Waits for `stream` and returns, then clears, the most severe condition the
+/* The error-bounded mode of Section 2.2 is a guarantee, so a call that could not keep it must be
+ * able to say so: waits for `stream` and returns, then clears, the most severe condition the
  * GPU recorded for this context since the last query: a negative error code, else
- * CMP_W_RANGE, else CMP_OK. */
+ * CMP_W_RANGE (values outside the quantiser's range were clamped: the bound does not hold for
+ * them), else CMP_OK. */
 int cmp_last_status(cmp_ctx *ctx, void *stream);
 
-/* Intermediate results of the LAST cmp_compress on this context, for parity
- * checks.  Stores a device pointer into the context's scratch (valid until the
- * next call on the context) and its size in bytes.  The caller synchronises. */
+/* Intermediate results of the LAST cmp_compress on this context, one per stage of Section 3.1
+ * (quantisation codes and outliers after prediction, histogram, Huffman code lengths and codes),
+ * for parity checks.  Stores a device pointer into the context's scratch (valid until the
+ * next call on the context) and its size in bytes.  The caller synchronises.  CMP_E_ARG for an
+ * unknown stage, for NULL pointers, and for the outlier stages before the first compress. */
 #define CMP_STAGE_QUANT_CODES 0   /* uint16[numel]: symbol per element, 0 = outlier (waits for the GPU) */
 #define CMP_STAGE_HIST        1   /* uint32[2*radius]: occurrences of each symbol              */
 #define CMP_STAGE_LENS        2   /* uint8[2*radius]: Huffman code length, 0 = unused          */
@@ -279,6 +291,8 @@ int cmp_estimate_eb(cmp_ctx *ctx, const float *d_act, uint64_t act_numel, const 
                     uint64_t per_sample, const float *d_mom, uint64_t mom_numel, const cmp_controller_config *cfg,
                     float *h_eb, double *h_stats, void *stream);
 
+/* A static English string for a return code of this library (the conditions listed at the top:
+ * what broke the guarantee of Section 2.2 or the container of Section 3.1); never NULL. */
 const char *cmp_strerror(int code);
 
 #ifdef __cplusplus

@@ -159,11 +159,12 @@ class ActivationCompressor:
 
     def check(self) -> dict:
         """Waits for the GPU.  Raises if a push did not fit or a pop met a damaged container;
-        returns the stack's figures: bytes in use, their peak, slots held."""
+        returns the stack's figures: bytes in use, their peak, slots held, and the status of the
+        calls so far (CMP_W_RANGE: some activation lay outside the quantiser's range and was clamped)."""
         rc, top, peak, held, failed = binding.cmp_arena_stats(self.ctx._h, self.state.data_ptr(), self._stream())
         st = self.ctx.last_status()
         if failed:
             raise MemoryError(f"activation stack: {failed} container(s) did not fit into {self.capacity} bytes")
         if st < 0:
             raise binding.CmpError(st, "activation stack")
-        return {"top": top, "peak": peak, "held": held}
+        return {"top": top, "peak": peak, "held": held, "status": st}
