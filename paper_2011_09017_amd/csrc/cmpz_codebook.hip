@@ -6,10 +6,9 @@
 // the lighter head is taken, a leaf before an internal node of equal weight.
 // Codes are canonical: ordered by (length, symbol), first code 0, read MSB first.
 //
-// Only the merge itself is serial (one lane, n-1 steps for n used symbols); it
-// keeps the heads of both queues in registers and fetches their successors one
-// step ahead, so a step costs ALU time only.  Sorting is by counting ranks,
-// depths by walking parent links, ranks within a length by wave ballots.
+// The merge runs in rounds that join up to 32 pairs at once (see step 4).  Sorting is by
+// counting ranks in blocks of 64 and binary search across blocks, depths by walking parent
+// links, ranks within a length by wave ballots.
 #include "cmpz_internal.h"
 
 namespace cmpz {
@@ -23,6 +22,14 @@ __device__ __forceinline__ uint32_t rdlane(uint32_t v, uint32_t l)
     return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)l);
 }
 
+// LDS written by some lanes of a wave is read by others: the hardware keeps a wave's LDS
+// operations in order, this keeps the compiler from moving them across.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 __global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
 {
     // one workgroup per tensor of the group
@@ -31,11 +38,12 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
     const OutRef oref = resolve_out(b.t[ti]);
     uint8_t *__restrict__ out = oref.out;
     __shared__ uint64_t key[kMaxSym];            // used symbols, compacted: count << 10 | symbol
+    __shared__ uint64_t skey[kMaxSym];           // the same, every block of 64 in ascending order
     __shared__ uint32_t leaf_w[kMaxSym + 192];   // leaf weights, ascending, padded with kInf
     __shared__ uint16_t leaf_sym[kMaxSym];
     __shared__ uint32_t node_w[kMaxSym + 192];   // internal node weights in creation order, kInf = not made
     __shared__ uint16_t parent[2 * kMaxSym];     // node ids: leaves 0..n-1, internal n..2n-2
-    __shared__ uint32_t merge_log[kMaxSym + 64]; // children of each internal node, two 16-bit ids
+    __shared__ uint32_t pair_w[64];              // weights of a round's nodes in their common order
     __shared__ uint32_t len_of[kMaxSym];         // code length per symbol
     __shared__ uint32_t wave_cnt[16][64];
     __shared__ uint32_t bl_count[64];
@@ -68,12 +76,34 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
     if (cnt) key[my_slot] = ((uint64_t)cnt << 10) | (uint64_t)tid;
     __syncthreads();
 
-    // 3. sort by counting: the rank of a key is the number of smaller keys (keys are distinct)
-    if ((uint32_t)tid < n) {
-        const uint64_t mine = key[tid];
-        uint32_t rank = 0;
+    // 3. sort (keys are distinct).  Every wave orders its own 64 keys by counting the smaller ones
+    //    among them; the rank of a key is then its place in its own block plus, by binary search,
+    //    the number of smaller keys in every other block.
+    const uint32_t nblocks = (n + 63u) >> 6;                         // uniform
+    const uint64_t mine = ((uint32_t)tid < n) ? key[tid] : ~0ull;    // past the end: heavier than any key
+    uint32_t in_block = (uint32_t)lane;
+    if ((uint32_t)wv < nblocks) {
+        if ((uint32_t)tid < n) {
+            const uint32_t first = (uint32_t)wv << 6;
+            const uint32_t here = (n - first < 64u) ? n - first : 64u;
+            in_block = 0;
 #pragma unroll 8
-        for (uint32_t j = 0; j < n; ++j) rank += (key[j] < mine) ? 1u : 0u;
+            for (uint32_t j = 0; j < here; ++j) in_block += (key[first + j] < mine) ? 1u : 0u;
+        }
+        skey[((uint32_t)wv << 6) + in_block] = mine;
+    }
+    __syncthreads();
+    if ((uint32_t)tid < n) {
+        uint32_t rank = in_block;
+        for (uint32_t w = 0; w < nblocks; ++w) {
+            if (w == (uint32_t)wv) continue;                         // uniform
+            const uint64_t *blk = skey + (w << 6);
+            uint32_t pos = 0;
+#pragma unroll
+            for (uint32_t step = 32; step >= 1; step >>= 1) pos += (blk[pos + step - 1] < mine) ? step : 0u;
+            pos += (blk[pos] < mine) ? 1u : 0u;                      // a count of 63 may be 64
+            rank += pos;
+        }
         leaf_w[rank] = (uint32_t)(mine >> 10);
         leaf_sym[rank] = (uint16_t)(mine & 1023u);
     }
@@ -82,123 +112,60 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
     if (tid < 192) node_w[kMaxSym + tid] = kInf;
     __syncthreads();
 
-    // 4. two-queue merge by wave 0.  Lane j of LB holds the weight of leaf lbase+j, lane j of IB
-    //    that of internal node ibase+j (kInf = not made yet).  The two lightest unused nodes of
-    //    either queue are kept in scalar registers; step m makes internal node m and logs its
-    //    weight and its two children in lane m%64 of WLOG / PLOG, which go to LDS once per 64
-    //    steps.  A lone wave pays about six cycles per instruction whatever its kind, so the steps
-    //    between two window slides run in a hand-written loop of about 25 scalar and lane
-    //    instructions (the compiler's version of the same step has about 70).
+    // 4. the two-queue merge, by wave 0, in rounds of up to 32 nodes.  The sequential rule takes the
+    //    unused nodes of both queues in one fixed order -- by weight, a leaf before an internal node
+    //    of the same weight, each queue in its own order -- and joins them two by two.  A node made
+    //    now weighs at least t, the sum of the two lightest unused nodes, and queues up behind every
+    //    node that exists already; so all unused nodes of weight <= t keep their places in that
+    //    order whatever is made from them, and a whole round of them can be joined at once: every
+    //    lane looks at one leaf and one internal node of the 64 next of either queue, finds their
+    //    places in the common order by binary search in the other queue, and the pairs (0,1), (2,3),
+    //    ... become the new nodes, already in order of weight.  Activation histograms need about
+    //    twenty rounds where the sequential rule needs hundreds of steps.
     if (__builtin_amdgcn_readfirstlane(wv) == 0 && __builtin_amdgcn_readfirstlane((int)n) >= 2) {
-        uint32_t LB = leaf_w[lane], IB = kInf, WLOG = kInf, PLOG = 0;
-        uint32_t lbase = 0, ibase = 0, ql = 0, qi = 0, m = 0;
-        uint32_t l0 = rdlane(LB, 0), l1 = rdlane(LB, 1), i0 = kInf, i1 = kInf;
         const uint32_t nu = (uint32_t)__builtin_amdgcn_readfirstlane((int)n);   // n came from LDS: tell the compiler it is uniform
         const uint32_t steps = nu - 1;
+        uint32_t ql = 0, qi = 0, m = 0;                      // leaves used, internal nodes used, internal nodes made
         while (m < steps) {
-            // rare: start a new log block, slide a window (heads are re-read from the new window)
-            if ((m & 63u) == 0 && m != 0) {
-                node_w[m - 64 + lane] = WLOG; merge_log[m - 64 + lane] = PLOG;
-                WLOG = kInf;
+            const uint32_t *lw = leaf_w + ql, *iw = node_w + qi;
+            const uint32_t LB = lw[lane];                    // kInf past the last leaf
+            const uint32_t IB = iw[lane];                    // kInf at and past node m
+            const uint64_t l0 = rdlane(LB, 0), l1 = rdlane(LB, 1), i0 = rdlane(IB, 0), i1 = rdlane(IB, 1);
+            uint64_t t = l0 + l1;                            // the two lightest of the four heads
+            t = (l0 + i0 < t) ? l0 + i0 : t;
+            t = (i0 + i1 < t) ? i0 + i1 : t;
+            const uint32_t t32 = (t < (uint64_t)kInf) ? (uint32_t)t : kInf - 1u;
+            const bool inL = LB <= t32, inI = IB <= t32;     // a prefix of either window
+            // places in the common order: internal nodes lighter than the leaf come before it, leaves
+            // no heavier than the internal node before that one.  Counts are exact up to 64, and a
+            // node with 64 others in front of it is not part of this round anyway.
+            uint32_t before_leaf = 0, before_node = 0;
+#pragma unroll
+            for (uint32_t step = 32; step >= 1; step >>= 1) {
+                const uint32_t a = iw[before_leaf + step - 1], c = lw[before_node + step - 1];
+                before_leaf += (a < LB) ? step : 0u;
+                before_node += (c <= IB) ? step : 0u;
             }
-            if (ql - lbase >= 32) {
-                lbase = ql; LB = leaf_w[ql + lane];
-                l0 = rdlane(LB, 0); l1 = rdlane(LB, 1);
+            {
+                const uint32_t a = iw[before_leaf], c = lw[before_node];    // counts of 63 may be 64
+                before_leaf += (a < LB) ? 1u : 0u;
+                before_node += (c <= IB) ? 1u : 0u;
             }
-            if (qi - ibase >= 32) {
-                // every node made so far must be readable from LDS: flush the open log block too
-                node_w[(m & ~63u) + lane] = WLOG;
-                ibase = qi;
-                IB = node_w[qi + lane];                     // entries at or past m are still kInf
-                i0 = rdlane(IB, 0); i1 = rdlane(IB, 1);
-            }
-            uint32_t lrel = ql - lbase, irel = qi - ibase, slot = m & 63u, mrel = m - ibase;
-            // steps that need no slide and no flush: both windows are read at most one lane past
-            // their head, which advances by at most two per step
-            uint32_t cnt = steps - m;
-            cnt = cnt < 64 - slot ? cnt : 64 - slot;
-            cnt = cnt < (62 - lrel) / 2 ? cnt : (62 - lrel) / 2;
-            cnt = cnt < (62 - irel) / 2 ? cnt : (62 - irel) / 2;
-            m += cnt;
-            // every scalar operand of the loop below, made provably uniform (a few moves per ~20 steps)
-            auto uni = [](uint32_t &v) { v = (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
-            uni(l0); uni(l1); uni(i0); uni(i1); uni(ql); uni(qi); uni(lrel); uni(irel); uni(slot); uni(mrel); uni(cnt);
-            uint32_t t1, t2, ws, kd, m0_saved;
-            asm volatile(
-                "s_mov_b32 %[sv], m0\n"
-                "s_nop 3\n"                                        // lane selects below were written by vector moves
-                "1:\n"
-                "  s_cmp_le_u32 %[l1], %[i0]\n"                    // a leaf wins ties
-                "  s_cbranch_scc0 2f\n"
-                "  s_add_u32 %[ws], %[l0], %[l1]\n"               // two leaves
-                "  s_add_u32 %[t1], %[ql], 1\n"
-                "  s_lshl_b32 %[t1], %[t1], 16\n"
-                "  s_or_b32 %[kd], %[t1], %[ql]\n"
-                "  s_add_u32 %[ql], %[ql], 2\n"
-                "  s_add_u32 %[lrel], %[lrel], 2\n"
-                "  s_add_u32 %[t1], %[lrel], 1\n"
-                "  v_readlane_b32 %[l0], %[LB], %[lrel]\n"
-                "  v_readlane_b32 %[l1], %[LB], %[t1]\n"
-                "  s_branch 4f\n"
-                "2:\n"
-                "  s_cmp_lt_u32 %[i1], %[l0]\n"
-                "  s_cbranch_scc0 3f\n"
-                "  s_add_u32 %[ws], %[i0], %[i1]\n"               // two internal nodes
-                "  s_add_u32 %[t1], %[n], %[qi]\n"
-                "  s_add_u32 %[t2], %[t1], 1\n"
-                "  s_lshl_b32 %[t2], %[t2], 16\n"
-                "  s_or_b32 %[kd], %[t2], %[t1]\n"
-                "  s_add_u32 %[qi], %[qi], 2\n"
-                "  s_add_u32 %[irel], %[irel], 2\n"
-                "  s_branch 4f\n"
-                "3:\n"
-                "  s_add_u32 %[ws], %[l0], %[i0]\n"               // one of each
-                "  s_add_u32 %[t1], %[n], %[qi]\n"
-                "  s_lshl_b32 %[t1], %[t1], 16\n"
-                "  s_or_b32 %[kd], %[t1], %[ql]\n"
-                "  s_add_u32 %[ql], %[ql], 1\n"
-                "  s_add_u32 %[qi], %[qi], 1\n"
-                "  s_add_u32 %[lrel], %[lrel], 1\n"
-                "  s_add_u32 %[irel], %[irel], 1\n"
-                "  s_mov_b32 %[l0], %[l1]\n"
-                "  s_add_u32 %[t1], %[lrel], 1\n"
-                "  v_readlane_b32 %[l1], %[LB], %[t1]\n"
-                "4:\n"
-                "  s_mov_b32 m0, %[slot]\n"                        // log node m
-                "  s_nop 0\n"
-                "  v_writelane_b32 %[WL], %[ws], m0\n"
-                "  v_writelane_b32 %[PL], %[kd], m0\n"
-                "  s_cmp_lt_u32 %[mrel], 64\n"
-                "  s_cbranch_scc0 5f\n"
-                "  s_mov_b32 m0, %[mrel]\n"                        // and make it visible to the internal queue
-                "  s_nop 0\n"
-                "  v_writelane_b32 %[IB], %[ws], m0\n"
-                "5:\n"
-                "  s_add_u32 %[t1], %[irel], 1\n"
-                "  v_readlane_b32 %[i0], %[IB], %[irel]\n"
-                "  v_readlane_b32 %[i1], %[IB], %[t1]\n"
-                "  s_add_u32 %[slot], %[slot], 1\n"
-                "  s_add_u32 %[mrel], %[mrel], 1\n"
-                "  s_sub_u32 %[cnt], %[cnt], 1\n"
-                "  s_cmp_lg_u32 %[cnt], 0\n"
-                "  s_cbranch_scc1 1b\n"
-                "  s_mov_b32 m0, %[sv]\n"
-                : [l0] "+s"(l0), [l1] "+s"(l1), [i0] "+s"(i0), [i1] "+s"(i1), [ql] "+s"(ql), [qi] "+s"(qi),
-                  [lrel] "+s"(lrel), [irel] "+s"(irel), [slot] "+s"(slot), [mrel] "+s"(mrel), [cnt] "+s"(cnt),
-                  [IB] "+v"(IB), [WL] "+v"(WLOG), [PL] "+v"(PLOG),
-                  [t1] "=&s"(t1), [t2] "=&s"(t2), [ws] "=&s"(ws), [kd] "=&s"(kd), [sv] "=&s"(m0_saved)
-                : [LB] "v"(LB), [n] "s"(nu)
-                : "scc", "memory");
+            const uint32_t rank_leaf = (uint32_t)lane + before_leaf, rank_node = (uint32_t)lane + before_node;
+            const uint32_t avail = (uint32_t)__popcll(__ballot(inL)) + (uint32_t)__popcll(__ballot(inI));
+            uint32_t npairs = avail >> 1;
+            npairs = npairs < 32u ? npairs : 32u;
+            npairs = npairs < steps - m ? npairs : steps - m;
+            const bool use_leaf = inL && rank_leaf < 2u * npairs, use_node = inI && rank_node < 2u * npairs;
+            if (use_leaf) { pair_w[rank_leaf] = LB; parent[ql + lane] = (uint16_t)(nu + m + (rank_leaf >> 1)); }
+            if (use_node) { pair_w[rank_node] = IB; parent[nu + qi + lane] = (uint16_t)(nu + m + (rank_node >> 1)); }
+            wave_lds_sync();
+            if ((uint32_t)lane < npairs) node_w[m + lane] = pair_w[2 * lane] + pair_w[2 * lane + 1];
+            wave_lds_sync();
+            ql += (uint32_t)__popcll(__ballot(use_leaf));
+            qi += (uint32_t)__popcll(__ballot(use_node));
+            m += npairs;
         }
-        const uint32_t blk = (steps - 1) & ~63u;             // the open log block
-        node_w[blk + lane] = WLOG; merge_log[blk + lane] = PLOG;
-    }
-    __syncthreads();
-    // parents from the log: step m made node n+m out of the two logged children
-    if ((uint32_t)tid + 1 < n) {
-        const uint32_t kids = merge_log[tid];
-        parent[kids & 0xffffu] = (uint16_t)(n + tid);
-        parent[kids >> 16] = (uint16_t)(n + tid);
     }
     __syncthreads();
 

@@ -293,6 +293,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
     __shared__ uint64_t table[kMaxSym + 1];          // length << 56 | code; or, as 32-bit words, code << (32 - length) | length
     __shared__ __align__(16) uint32_t images[kWaves][kImageWords];
     __shared__ uint32_t coff_s[kPackChunks], ooff_s[kPackChunks + 1], bits_s[kPackChunks];
+    __shared__ uint16_t olists[kWaves][kWave];       // per wave: where in a step the outliers of one pass sit
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t ti = tensor_of_range(b, blockIdx.x);
@@ -315,6 +316,7 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
         for (int k = tid; k <= (int)kMaxSym; k += kThreads) table[k] = (k < (int)kMaxSym) ? src[k] : 0ull;
     }
     uint32_t *img = images[wv];
+    uint16_t *olist = olists[wv];
     for (uint32_t k = lane; k < kImageUnits; k += kWave) reinterpret_cast<uint4 *>(img)[k] = make_uint4(0, 0, 0, 0);
 
     // where the range's chunks and their outlier records start
@@ -358,27 +360,38 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
         // one step: the lane's n consecutive symbols s[] starting at element i0
         auto step = [&](const uint32_t *s, auto n_c, uint32_t i0, bool last) {
             constexpr int n = decltype(n_c)::value;
-            // outlier records: rank the zero symbols, recompute their residuals from x
+            // outlier records: rank the zero symbols of the step; then one lane per outlier recomputes
+            // its residual from x, so that the loads of all of them are in flight together
             if (has_outl) {
                 uint32_t mine = 0;
                 _Pragma("unroll") for (int k = 0; k < n; ++k) mine += (s[k] == 0u) ? 1u : 0u;
                 const uint32_t inc = wave_inclusive_sum(mine);
-                uint32_t at = orank + inc - mine;
-                if (mine) {
+                const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+                const uint32_t step0 = i0 - (uint32_t)lane * (uint32_t)n;          // first element of the step
+                for (uint32_t r0 = 0; r0 < total; r0 += kWave) {                 // uniform; one pass unless outliers crowd
+                    uint32_t rk = inc - mine - r0;                               // place of the lane's next outlier in this pass
                     _Pragma("unroll") for (int k = 0; k < n; ++k) {
-                        if (s[k] != 0u) continue;
-                        const uint32_t i = i0 + k;
+                        if (s[k] == 0u) {
+                            if (rk < (uint32_t)kWave) olist[rk] = (uint16_t)(lane * n + k);
+                            ++rk;
+                        }
+                    }
+                    wave_sync();
+                    const uint32_t me = r0 + (uint32_t)lane;
+                    if (me < total) {
+                        const uint32_t i = step0 + olist[lane];
                         const uint32_t p = tc.divHW.div(i);
                         const uint32_t rem = i - p * HW;
                         const uint32_t h = tc.divW.div(rem), w = rem - h * W;
+                        const uint32_t at = orank + me;
                         if (at < tm.n_outliers) {
                             oidx[at] = i;
                             oval[at] = delta_from_x(x, i, h, w, W, tc.r);
                         }
-                        ++at;
                     }
+                    wave_sync();
                 }
-                orank += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+                orank += total;
             }
             // version 2: a sub-block of zero residuals (n symbols per lane: sub / n lanes) has no bits
             bool coded = true;
