@@ -154,6 +154,31 @@ class Run:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    def time_graph(self, steps):
+        """One step captured into a HIP graph (the calls allocate nothing and never wait), replayed."""
+        torch = self.torch
+        assert self.api == "batch"
+        side = torch.cuda.Stream(self.xs[0].device)          # default priority
+        saved = self.streams
+        self.streams = [side.cuda_stream]
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.step()                                      # once eagerly on the capturing stream
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            self.step()
+        self.streams = saved
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        self.check()                                         # what the replays left is a valid round trip
+        return ms
+
     def time_phases(self, steps):
         """Per-phase times (host clock, a device-wide wait after each phase)."""
         torch = self.torch
@@ -358,6 +383,10 @@ def main() -> int:
             "sample": f"first {checked} tensors of {wl.name} ({n_s} elements), "
                       f"compress {t_c:.2f} s + decompress {t_d:.2f} s, host has {os.cpu_count()} cpus"}
         result["parity_checked_tensors"] = checked
+    if not args.no_extras and run.api == "batch":
+        g_ms = run.time_graph(args.steps)
+        result["graph_replay"] = {"ms_per_step": round(g_ms, 4), "GBps": round(2 * 4.0 * total / (g_ms * 1e-3) / 1e9, 2),
+                                  "what": "the same step (both batch calls) captured once into a HIP graph and replayed"}
     run.free()
 
     # ---- extras ------------------------------------------------------------------------

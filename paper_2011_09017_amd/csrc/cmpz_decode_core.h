@@ -346,7 +346,7 @@ template <class PUT>
 __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint32_t *S, uint32_t pos,
                                                uint32_t count, uint32_t skip, PUT put, bool &bad)
 {
-    const uint32_t t32 = T.t32, sh = T.sh, has_long = T.has_long;
+    const uint32_t t32 = T.t32, sh = T.sh;
     const char *t1 = reinterpret_cast<const char *>(T.t1);
     // The three stream words around the position live in registers: wa, wb are the window of the
     // current codeword, wc the word after them.  A codeword of the first two table levels is at
@@ -361,7 +361,8 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
         const uint32_t hi = __builtin_amdgcn_alignbit(wa, wb, npos);
         uint32_t e = *reinterpret_cast<const uint16_t *>(t1 + ((hi >> (31 - kLB)) & (2u * kT1Size - 2u)));
         if (e == 0) {
-            if (has_long) {
+            {
+                // (a codebook without long codes has a second table of zeros: no test for that case)
                 uint32_t i2 = (hi - t32) >> sh;
                 i2 = i2 < kT2Size ? i2 : kT2Size - 1;
                 e = T.t2[i2];

@@ -22,6 +22,15 @@ constexpr int kThreads = 256;
 constexpr int kHalo    = 1040;                    // LDS slots in front of the chunk; needs W + 4 <= kHalo
 constexpr int kQWords  = kHalo + (int)kChunk + 16;
 
+// Bit k of m as a mask of all ones or all zeros.  The empty asm keeps the compiler from turning
+// the AND with it into a compare and a select (three instructions and a wait state for two).
+__device__ __forceinline__ int mask_of_bit(int m, int k)
+{
+    int r = __builtin_amdgcn_sbfe(m, k, 1);
+    asm("" : "+v"(r));
+    return r;
+}
+
 __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(BatchC b)
 {
     __shared__ __align__(16) int16_t Q[kQWords];
@@ -99,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
         const uint32_t g0 = t0 + i0;
         uint32_t s[16];
         uint32_t nout = 0;
-        uint32_t bytes_or = 0;                                       // OR of symbol - sym_off over the thread's elements
+        uint32_t bytes_or = 0;                                       // above 0xff: some symbol of the thread has no byte form
         uint32_t zeros = 0, nhere = 0;                               // zero residuals among the thread's elements; how many it has
         if (g0 < t1) {
             // plane coordinates of the first element, then bit masks over the 16 elements:
@@ -139,23 +148,30 @@ __global__ __launch_bounds__(kThreads) void k_quant_lorenzo_split_hist_tiled(Bat
             const uint32_t nval = (t1 - g0 >= 16u) ? 16u : t1 - g0;
             nhere = nval;
             if (nval == 16u) {
-                // all 16 elements exist: symbols first, the in-range test on the largest of them
-                uint32_t top = 0;
+                // all 16 elements exist.  With v = q - (q of the row above, 0 in the first row) the
+                // residual is v[k] - v[k-1], the second term 0 at a row start (an element that does not
+                // start a row lies in the row of its left neighbour, so the neighbour's v may be taken
+                // with this element's first-row mask).  Symbols first; the in-range test and the test
+                // for the byte form on the smallest and the largest of them.
+                const int nmw = (int)~mw, nmh = (int)~mh;                        // bit k set: keep the term
+                int vprev = cur[0] - (up[0] & mask_of_bit(nmh, 0));
+                int smax = -0x7fffffff, smin = 0x7fffffff;
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
-                    const int keepw = ~__builtin_amdgcn_sbfe((int)mw, k, 1);     // 0 where the row starts
-                    const int keeph = ~__builtin_amdgcn_sbfe((int)mh, k, 1);     // 0 in the first row
-                    const int d = (cur[k + 1] - (cur[k] & keepw)) - ((up[k + 1] - (up[k] & keepw)) & keeph);
-                    s[k] = (uint32_t)(d + R);
-                    const uint32_t v1 = s[k] - 1u;                               // in range: 0 <= v1 < 2R-1
-                    top = v1 > top ? v1 : top;
-                    bytes_or |= s[k] - b.sym_off;
+                    const int vk = cur[k + 1] - (up[k + 1] & mask_of_bit(nmh, k));
+                    const int sk = (vk + R) - (vprev & mask_of_bit(nmw, k));
+                    vprev = vk;
+                    s[k] = (uint32_t)sk;
+                    smax = sk > smax ? sk : smax;
+                    smin = sk < smin ? sk : smin;
                 }
-                if (top >= (uint32_t)(2 * R - 1)) {                              // rare: some residual is an outlier
+                if (smin < 1 || smax > 2 * R - 1) {                              // rare: some residual is an outlier
 #pragma unroll
                     for (int k = 0; k < 16; ++k)
                         if (s[k] - 1u >= (uint32_t)(2 * R - 1)) { s[k] = 0u; ++nout; }
                     bytes_or = 0x100u;                                           // the outlier symbol has no byte form
+                } else if (smin < (int)b.sym_off || smax > (int)b.sym_off + 255) {
+                    bytes_or = 0x100u;
                 }
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
