@@ -288,7 +288,7 @@ constexpr uint32_t kImageUnits = kStepBitsMax / 128 + 2;               // the op
 constexpr uint32_t kImageWords = kImageUnits * 4;
 
 template <bool ZB>
-__global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
+__global__ __launch_bounds__(kThreads, ZB ? 4 : 6) void k_pack(BatchC b)
 {
     __shared__ uint64_t table[kMaxSym + 1];          // length << 56 | code; or, as 32-bit words, code << (32 - length) | length
     __shared__ __align__(16) uint32_t images[kWaves][kImageWords];
@@ -408,18 +408,42 @@ __global__ __launch_bounds__(kThreads) void k_pack(BatchC b)
             const uint32_t inc = wave_inclusive_sum(bits);
             uint32_t pos = bitpos - ubase * 128u + inc - bits;        // bit position in the image
             if (short_codes) {
-                // two codewords (at most 54 bits together) go into the image as one: three LDS atomics per pair
-                _Pragma("unroll") for (int k = 0; k < n; k += 2) {
-                    const uint32_t c0 = e[k] & ~31u, l0 = e[k] & 31u;               // left-aligned codes
-                    const uint32_t c1 = e[k + 1] & ~31u, l1 = e[k + 1] & 31u;
-                    const uint64_t second = (((uint64_t)c1) << 32) >> l0;
-                    const uint32_t hi = c0 | (uint32_t)(second >> 32), lo = (uint32_t)second;
+                // Codewords go into the image in groups: two of them (at most 54 bits together) merged
+                // in registers cost three LDS atomics, and so do four when they fit 64 bits, which they
+                // nearly always do (uniform test over the wave; otherwise two by two).
+                uint32_t longest = 0;
+                _Pragma("unroll") for (int k = 0; k < n; k += 4) {
+                    const uint32_t tot = (e[k] & 31u) + (e[k + 1] & 31u) + (e[k + 2] & 31u) + (e[k + 3] & 31u);
+                    longest = tot > longest ? tot : longest;
+                }
+                auto pair_of = [](uint32_t ea, uint32_t eb, uint32_t &hi, uint32_t &lo, uint32_t &len) {
+                    const uint32_t ca = ea & ~31u, la = ea & 31u;                   // left-aligned codes
+                    const uint64_t second = (((uint64_t)(eb & ~31u)) << 32) >> la;
+                    hi = ca | (uint32_t)(second >> 32); lo = (uint32_t)second; len = la + (eb & 31u);
+                };
+                auto put = [&](uint32_t hi, uint32_t lo) {
                     const uint32_t o = pos & 31u;
                     uint32_t *w = img + (pos >> 5);
                     atomicOr(w, hi >> o);
                     atomicOr(w + 1, __builtin_amdgcn_alignbit(hi, lo, o));
                     atomicOr(w + 2, __builtin_amdgcn_alignbit(lo, 0u, o));           // the part that spills over
-                    pos += l0 + l1;
+                };
+                if (!__any(longest > 64u)) {
+                    _Pragma("unroll") for (int k = 0; k < n; k += 4) {
+                        uint32_t h0, l0, n0, h1, l1, n1;
+                        pair_of(e[k], e[k + 1], h0, l0, n0);
+                        pair_of(e[k + 2], e[k + 3], h1, l1, n1);
+                        const uint64_t quad = (((uint64_t)h0 << 32) | l0) | ((((uint64_t)h1 << 32) | l1) >> n0);   // n0 <= 54
+                        put((uint32_t)(quad >> 32), (uint32_t)quad);
+                        pos += n0 + n1;
+                    }
+                } else {
+                    _Pragma("unroll") for (int k = 0; k < n; k += 2) {
+                        uint32_t h0, l0, n0;
+                        pair_of(e[k], e[k + 1], h0, l0, n0);
+                        put(h0, l0);
+                        pos += n0;
+                    }
                 }
             } else {
                 _Pragma("unroll") for (int k = 0; k < n; ++k) {
