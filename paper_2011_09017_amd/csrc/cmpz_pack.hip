@@ -141,13 +141,22 @@ __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
                 const uint32_t i0 = e0 + 1024u * qt + (uint32_t)lane * 16u;
                 uint32_t bits = 0;
                 bool az = true;
+                if (full) {                                  // uniform; every chunk of a tensor but its last
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    const uint32_t byte = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
-                    const uint32_t len = Lo[byte];
-                    const bool there = full || i0 + k < numel;
-                    bits += there ? len : 0u;
-                    az = az && (!there || byte + b.sym_off == b.radius);
+                    for (int k = 0; k < 16; ++k) {
+                        const uint32_t byte = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
+                        bits += Lo[byte];
+                        if (ZB) az = az && (byte + b.sym_off == b.radius);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const uint32_t byte = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
+                        const uint32_t len = Lo[byte];
+                        const bool there = i0 + k < numel;
+                        bits += there ? len : 0u;
+                        az = az && (!there || byte + b.sym_off == b.radius);
+                    }
                 }
                 if (ZB && group_all(az, (uint32_t)lane, b.sub / 16)) bits = 0;
                 emit(bits, (1024u * qt) / b.sub, b.sub / 16);
@@ -357,12 +366,17 @@ __global__ __launch_bounds__(kThreads, ZB ? 4 : 6) void k_pack(BatchC b)
         uint32_t bitpos = 0;                         // bits of the chunk packed so far
         uint32_t ubase = 0;                          // units of the chunk stored so far: image unit 0 is stream unit ubase
 
-        // one step: the lane's n consecutive symbols s[] starting at element i0
-        auto step = [&](const uint32_t *s, auto n_c, uint32_t i0, bool last) {
+        // one step: the lane's n consecutive symbols s[] starting at element i0.  narrow: s[] holds the
+        // bytes of a quarter stored with 8 bits per symbol, i.e. symbol - sym_off (no outlier among them)
+        auto step = [&](const uint32_t *s, auto n_c, auto narrow_c, uint32_t i0, bool last) {
             constexpr int n = decltype(n_c)::value;
+            constexpr bool narrow = decltype(narrow_c)::value;
+            const uint32_t zero_sym = narrow ? b.radius - b.sym_off : b.radius;    // the zero residual, as s[] has it
+            const uint32_t past_sym = narrow ? kPastEnd - b.sym_off : kPastEnd;    // elements past the end of the tensor
+            const uint32_t *tab = narrow ? table32 + b.sym_off : table32;
             // outlier records: rank the zero symbols of the step; then one lane per outlier recomputes
             // its residual from x, so that the loads of all of them are in flight together
-            if (has_outl) {
+            if (!narrow && has_outl) {
                 uint32_t mine = 0;
                 _Pragma("unroll") for (int k = 0; k < n; ++k) mine += (s[k] == 0u) ? 1u : 0u;
                 const uint32_t inc = wave_inclusive_sum(mine);
@@ -397,13 +411,13 @@ __global__ __launch_bounds__(kThreads, ZB ? 4 : 6) void k_pack(BatchC b)
             bool coded = true;
             if (ZB) {
                 bool az = true;
-                _Pragma("unroll") for (int k = 0; k < n; ++k) az = az && (s[k] == b.radius || s[k] == kPastEnd);
+                _Pragma("unroll") for (int k = 0; k < n; ++k) az = az && (s[k] == zero_sym || s[k] == past_sym);
                 coded = !group_all(az, (uint32_t)lane, b.sub / (uint32_t)n);
             }
             // bit offsets of the lanes; in the short-code case the table entries stay in registers for the packing
             uint32_t bits = 0;
             uint32_t e[n];
-            if (short_codes) { _Pragma("unroll") for (int k = 0; k < n; ++k) { e[k] = coded ? table32[s[k]] : 0u; bits += e[k] & 31u; } }
+            if (short_codes) { _Pragma("unroll") for (int k = 0; k < n; ++k) { e[k] = coded ? tab[s[k]] : 0u; bits += e[k] & 31u; } }
             else             { _Pragma("unroll") for (int k = 0; k < n; ++k) bits += coded ? (uint32_t)(table[s[k]] >> 56) : 0u; }
             const uint32_t inc = wave_inclusive_sum(bits);
             uint32_t pos = bitpos - ubase * 128u + inc - bits;        // bit position in the image
@@ -511,13 +525,23 @@ __global__ __launch_bounds__(kThreads, ZB ? 4 : 6) void k_pack(BatchC b)
                 uint4 nlo, nhi;
                 fetch(it < 3 ? it + 1 : it, nlo, nhi);                    // the last step fetches its own symbols again
                 uint32_t s[16];
-                if (wide) { unpack8(lo, s); unpack8(hi, s + 8); }
-                else { unpack_bytes(lo.x, s); unpack_bytes(lo.y, s + 4); unpack_bytes(lo.z, s + 8); unpack_bytes(lo.w, s + 12); }
-                if (!full) {
+                if (wide) {
+                    unpack8(lo, s); unpack8(hi, s + 8);
+                    if (!full) {
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) if (i0 + k >= numel) s[k] = kPastEnd;
+                        for (int k = 0; k < 16; ++k) if (i0 + k >= numel) s[k] = kPastEnd;
+                    }
+                    step(s, std::integral_constant<int, 16>{}, std::false_type{}, i0, it == 3);
+                } else {
+                    const uint32_t w4[4] = {lo.x, lo.y, lo.z, lo.w};
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) s[k] = (w4[k >> 2] >> (8 * (k & 3))) & 0xffu;
+                    if (!full) {
+#pragma unroll
+                        for (int k = 0; k < 16; ++k) if (i0 + k >= numel) s[k] = kPastEnd - b.sym_off;
+                    }
+                    step(s, std::integral_constant<int, 16>{}, std::true_type{}, i0, it == 3);
                 }
-                step(s, std::integral_constant<int, 16>{}, i0, it == 3);
                 lo = nlo; hi = nhi;
             }
         } else {
@@ -537,7 +561,7 @@ __global__ __launch_bounds__(kThreads, ZB ? 4 : 6) void k_pack(BatchC b)
 #pragma unroll
                     for (int k = 0; k < 8; ++k) if (i0 + k >= numel) s[k] = kPastEnd;
                 }
-                step(s, std::integral_constant<int, 8>{}, i0, it == 7);
+                step(s, std::integral_constant<int, 8>{}, std::false_type{}, i0, it == 7);
             }
         }
         if (bitpos != bits_s[q]) failed = true;      // the two passes disagree: cannot happen
