@@ -156,6 +156,13 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
             uint32_t npairs = avail >> 1;
             npairs = npairs < 32u ? npairs : 32u;
             npairs = npairs < steps - m ? npairs : steps - m;
+            // the two lightest nodes always weigh <= t, so a round joins at least one pair; a histogram
+            // whose counts do not add up below 2^32 (damaged scratch memory) could break that: leave
+            // rather than spin
+            if (npairs == 0) {
+                if (lane == 0) atomicOr(b.status, kStInternal);
+                break;
+            }
             const bool use_leaf = inL && rank_leaf < 2u * npairs, use_node = inI && rank_node < 2u * npairs;
             if (use_leaf) { pair_w[rank_leaf] = LB; parent[ql + lane] = (uint16_t)(nu + m + (rank_leaf >> 1)); }
             if (use_node) { pair_w[rank_node] = IB; parent[nu + qi + lane] = (uint16_t)(nu + m + (rank_node >> 1)); }
@@ -175,7 +182,8 @@ __global__ __launch_bounds__(kCbThreads) void k_codebook(BatchC b)
         if (n == 1) depth = 1;
         else {
             const uint32_t root = 2 * n - 2;
-            for (uint32_t v = tid; v != root; v = parent[v]) ++depth;
+            // (bounded: a walk over a complete tree ends at the root after at most kMaxCodeLen steps)
+            for (uint32_t v = tid; v != root && depth < 64u; v = parent[v] & (2 * kMaxSym - 1)) ++depth;
         }
         len_of[leaf_sym[tid]] = depth;
         atomicAdd(&bl_count[depth & 63u], 1u);
