@@ -1,5 +1,5 @@
 // Huffman codebook on the GPU: histogram -> code lengths -> canonical codes.
-// One workgroup; no host round trip between the two sweeps of a compress.
+// One workgroup per tensor; no host round trip between the two sweeps of a compress.
 //
 // Rule (fixes one of the equally optimal codebooks): leaves sorted ascending by
 // (count, symbol); two FIFO queues, leaves and internal nodes in creation order;
@@ -15,7 +15,7 @@ namespace cmpz {
 namespace {
 
 constexpr int kCbThreads = 1024;
-constexpr uint32_t kInf = 0xffffffffu;       // "queue empty"; a real weight reaches it only at the root
+constexpr uint32_t kInf = 0xffffffffu;       // "no such node"; real weights stay below 2^32 - 8192, the largest tensor
 
 __device__ __forceinline__ uint32_t rdlane(uint32_t v, uint32_t l)
 {
