@@ -430,7 +430,9 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
 #pragma unroll
                 for (int q = 0; q < kRows; ++q) {
                     if (kFull || (uint32_t)q < nr) {
-                        const uint32_t uq = u + q * W, t = uq >> kLog;
+                        const uint32_t uq = u + q * W;
+                        uint32_t t = uq >> kLog;
+                        asm("" : "+v"(t));           // one shift serves both addresses below (else the compiler derives each from uq anew)
                         kk[q] = uq & (uint32_t)(SUB - 1);
                         t8[q] = R[uq + t]; rc[q] = RC[t];
                     }
@@ -439,7 +441,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
                 for (int q = 0; q < kRows; ++q) {
                     if (kFull || (uint32_t)q < nr) {
                         acc += t8[q] + ((kk[q] < rc[q].x) ? (int32_t)rc[q].y : 0);
-                        *reinterpret_cast<float *>(band_out + (off + q * 4u * W)) = (float)(int16_t)acc * s;
+                        // the row's offset is uniform: it goes to the scalar base, the lane keeps one offset
+                        *reinterpret_cast<float *>((band_out + (size_t)(q * 4u * W)) + off) = (float)(int16_t)acc * s;
                     }
                 }
             };
