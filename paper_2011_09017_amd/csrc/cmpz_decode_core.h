@@ -360,14 +360,14 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
     for (uint32_t k = 0; k < count; ++k) {
         const uint32_t hi = __builtin_amdgcn_alignbit(wa, wb, npos);
         uint32_t e = *reinterpret_cast<const uint16_t *>(t1 + ((hi >> (31 - kLB)) & (2u * kT1Size - 2u)));
-        if (e == 0) {
+        if (__builtin_expect(e == 0, 0)) {
             {
                 // (a codebook without long codes has a second table of zeros: no test for that case)
                 uint32_t i2 = (hi - t32) >> sh;
                 i2 = i2 < kT2Size ? i2 : kT2Size - 1;
                 e = T.t2[i2];
             }
-            if (e == 0) {
+            if (__builtin_expect(e == 0, 0)) {
                 // canonical search over the longer lengths on a 64-bit window
                 const uint32_t lo = __builtin_amdgcn_alignbit(wb, wc, npos);
                 const uint64_t v = (((uint64_t)hi) << 32) | lo;

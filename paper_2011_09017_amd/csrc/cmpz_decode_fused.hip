@@ -496,21 +496,29 @@ bool plan_decode_fused(TensorD *t, uint32_t sub)
     return true;
 }
 
-// One launch over the tensors of the group that have a plan.  Workgroups are dealt to the tensors
-// in proportion to their elements: about eight per CU in total, so that the chip's four resident
-// ones per CU are replaced as they finish and tensors of different cost per element even out;
-// no more than a tensor has items for, at least one.
-void launch_decode_fused(BatchD &b, Profiler *prof, hipStream_t st)
+// One launch over the tensors of the group that have a plan.  Four workgroups are resident per
+// compute unit.  A small call gets one round of them (a second round would build its decode tables
+// for little work); a large one up to six rounds, dealt to the tensors in proportion to their
+// elements, so that workgroups of different cost (small planes cost more per element than large
+// ones) even out and the chip does not idle while the last round's slowest workgroup finishes.
+// Measured on the ResNet-18-shaped stream (17 tensors, 591 M elements): 1.45 / 1.16 / 1.03 / 1.02 /
+// 1.05 / 1.23 ms for 1 / 2 / 4 / 6 / 16 / 64 rounds; single tensors of 37 M and 51 M elements: one
+// round 7 % faster than two.  No more than a tensor has items for, at least one.
+void launch_decode_fused(BatchD &b, uint32_t cus, Profiler *prof, hipStream_t st)
 {
     uint64_t total = 0;
     for (uint32_t k = 0; k < b.n; ++k) if (b.t[k].nitems) total += b.t[k].numel;
+    const uint64_t slots = 4ull * cus;
+    uint64_t rounds = total / (slots * 65536ull);            // at least 64 K elements per workgroup and round
+    rounds = rounds < 1 ? 1 : rounds > 6 ? 6 : rounds;
+    const uint64_t deal = slots * rounds;
     uint32_t grid = 0;
     for (uint32_t k = 0; k < b.n; ++k) {
         TensorD &t = b.t[k];
         t.wg_base = grid;
         t.nwg = 0;
         if (!t.nitems) continue;
-        const uint64_t share = ((uint64_t)t.numel * 2048 + total - 1) / total;
+        const uint64_t share = ((uint64_t)t.numel * deal + total - 1) / total;
         const uint64_t most = (t.nitems + kWaves - 1) / kWaves;
         t.nwg = (uint32_t)(share < most ? share : most);
         if (t.nwg < 1) t.nwg = 1;

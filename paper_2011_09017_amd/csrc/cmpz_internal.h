@@ -387,7 +387,7 @@ void launch_arena_release(ArenaState *st_dev, uint32_t slot, hipStream_t st);
 void launch_widen(uint16_t *sym, uint32_t *wide, uint32_t sym_off, uint32_t nchunks, hipStream_t st);
 size_t decode_tables_bytes();
 bool plan_decode_fused(TensorD *t, uint32_t sub);
-void launch_decode_fused(BatchD &b, Profiler *prof, hipStream_t st);
+void launch_decode_fused(BatchD &b, uint32_t cus, Profiler *prof, hipStream_t st);
 void launch_decompress_unfused(const DecompressArgs &a, void *tables, Profiler *prof, hipStream_t st);
 
 // Error-bound estimator: device scratch (zero between calls) and result record.
