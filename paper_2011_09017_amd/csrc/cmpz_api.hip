@@ -277,15 +277,15 @@ void group_add(BatchC *b, const CheckedTensor &c, void *d_out, size_t out_cap)
 // histogram, contended atomics), but still several per CU.  Tensors whose rows do not fit the
 // tiled kernel get none here and a launch of the untiled kernel each.
 // Workgroups of the first sweep: eight are resident per compute unit; a workgroup takes
-// sweep_chunks consecutive chunks of one tensor.  One round of them for a small call, up to eight
+// sweep_chunks consecutive chunks of one tensor.  One round of them for a small call, up to sixteen
 // rounds for a large one, so that the chip does not idle while the slowest workgroup of a single
 // round finishes (ResNet-18-shaped stream, 144 256 chunks: 0.89 / 0.68 / 0.67 / 0.66 / 0.64 / 0.63 ms
 // for 0.5 / 1 / 2 / 4 / 8 / 16 rounds).
 void group_plan_sweep(BatchC *b, uint32_t cus)
 {
     const uint32_t slots = 8u * cus;
-    uint32_t rounds = b->total_chunks / (slots * 8u);         // at least eight chunks per workgroup and round
-    rounds = rounds < 1 ? 1 : rounds > 8 ? 8 : rounds;
+    uint32_t rounds = b->total_chunks / (slots * 4u);         // at least four chunks per workgroup and round
+    rounds = rounds < 1 ? 1 : rounds > 16 ? 16 : rounds;
     const uint32_t want = slots * rounds;
     b->sweep_chunks = (b->total_chunks + want - 1) / want;
     if (b->sweep_chunks < 1) b->sweep_chunks = 1;

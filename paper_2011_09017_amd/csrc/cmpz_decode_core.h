@@ -354,8 +354,11 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
     // becomes wc is fetched a whole step before it can be needed: the only LDS access a step
     // has to wait for is the table look-up.
     uint32_t npos = 0u - pos;                                 // alignbit takes its shift from -pos mod 32
-    uint32_t J = (31u - npos) >> 5;                           // stream word J-1 holds bit pos (or ends just before it)
-    uint32_t wa = S[kStagePad - 1 + J], wb = S[kStagePad + J], wc = S[kStagePad + 1 + J];
+    // stream word J-1 holds bit pos (or ends just before it), J = ceil(pos / 32); kept as N = -J, which is
+    // one arithmetic shift of npos
+    int32_t N = (int32_t)npos >> 5;
+    const uint32_t *Sw = S + kStagePad;
+    uint32_t wa = Sw[-1 - N], wb = Sw[-N], wc = Sw[1 - N];
 #pragma unroll 4
     for (uint32_t k = 0; k < count; ++k) {
         const uint32_t hi = __builtin_amdgcn_alignbit(wa, wb, npos);
@@ -383,17 +386,17 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
                 if (len == 0) { bad = true; len = 1; }
                 e = sy | (len << 10);
                 // such a codeword may end two words further on: take the first of the two moves here
-                uint32_t Jf = (31u - (npos - len)) >> 5;
-                if (Jf > J + 1) { wa = wb; wb = wc; wc = S[kStagePad + 2 + J]; ++J; }
+                const int32_t Nf = (int32_t)(npos - len) >> 5;
+                if (Nf < N - 1) { wa = wb; wb = wc; wc = Sw[2 - N]; --N; }
             }
         }
         npos -= e >> 10;
-        uint32_t Jn = (31u - npos) >> 5;
-        const bool moved = Jn != J;
+        const int32_t Nn = (int32_t)npos >> 5;
+        const bool moved = Nn != N;
         wa = moved ? wb : wa;
         wb = moved ? wc : wb;
-        wc = S[kStagePad + 1 + Jn];
-        J = Jn;
+        wc = Sw[1 - Nn];
+        N = Nn;
         if (k >= skip) put(k, entry_residual(e));
     }
     return 0u - npos;

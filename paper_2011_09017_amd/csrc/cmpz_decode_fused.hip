@@ -337,8 +337,10 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
                     int32_t run = 0;
                     const uint32_t keep_mask = ~mask;
                     end = run_decode(32u, 0u, [&](uint32_t k, int32_t d) {
-                        const int32_t keep = __builtin_amdgcn_sbfe((int)keep_mask, k, 1); // 0 where the row restarts
-                        run = (run & keep) + d;
+                        // run * (0 where the row restarts, else 1) + d in one multiply-add: the sums of a
+                        // lane's 32 in-range residuals stay far inside 24 bits
+                        const uint32_t keep01 = __builtin_amdgcn_ubfe(keep_mask, k, 1);
+                        asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(run) : "v"(run), "v"(keep01), "v"(d));
                         my[k] = run;
                     });
                     my_tail = my[khi - 1];
