@@ -14,7 +14,7 @@
 namespace cmpz {
 
 constexpr uint32_t kT1Size = 1u << kLB;
-constexpr uint32_t kT2Bits = 9;
+constexpr uint32_t kT2Bits = 8;
 constexpr uint32_t kT2Size = 1u << kT2Bits;
 
 // Table entries: symbol in bits 0..9, code length in bits 10..15; 0 = not resolved here.
