@@ -62,9 +62,13 @@ __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
     __shared__ uint32_t bits_s[kPackChunks];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t ti = tensor_of_range(b, blockIdx.x);
+    // The ranges are taken last first: the first sweep wrote the symbols in ascending order, so what
+    // it wrote last is what the memory-side cache still holds; and what this pass reads last (the
+    // first ranges) is what the packing pass, which runs forwards, reads first.
+    const uint32_t range = b.pack_wgs - 1u - blockIdx.x;
+    const uint32_t ti = tensor_of_range(b, range);
     const TensorC &tc = b.t[ti];
-    const uint32_t c0 = (blockIdx.x - tc.pack_base) * kPackChunks;
+    const uint32_t c0 = (range - tc.pack_base) * kPackChunks;
     const uint32_t nq = (tc.nchunks - c0 < kPackChunks) ? tc.nchunks - c0 : kPackChunks;
     const uint32_t numel = tc.numel;
     static_assert(kMaxSym / 4 == kThreads, "one word of the length table per thread");
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void k_lengths(BatchC b)
         const uint32_t tu = wave_inclusive_sum((bits + 127u) >> 7);
         const uint32_t to = wave_inclusive_sum(oc);
         const uint32_t tb = wave_inclusive_sum(bits);
-        if (lane == 63) { b.range_units[blockIdx.x] = tu; b.range_outl[blockIdx.x] = to; b.range_bits[blockIdx.x] = tb; }
+        if (lane == 63) { b.range_units[range] = tu; b.range_outl[range] = to; b.range_bits[range] = tb; }
     }
 }
 
