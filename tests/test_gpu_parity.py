@@ -198,6 +198,54 @@ def test_long_codewords(gpu, orc, nsym):
     assert h["max_len"] == nsym - 1
 
 
+def _rows_from_residuals(d, s, width=64):
+    """Planes of one row each (1D Lorenzo): the residual sequence d, `width` per plane, as a tensor."""
+    q = np.cumsum(d.reshape(-1, width), axis=1)
+    assert np.abs(q).max() < 16384
+    return (q.astype(np.float32) * np.float32(s)).reshape(1, -1, 1, width)
+
+
+@pytest.mark.parametrize("sub", [32, 128])
+def test_rare_symbols_in_a_row(gpu, orc, sub):
+    """Residual counts 1, 1, 2, 4, ..., 2^19: codewords of up to twenty bits, and the rarest residuals
+    next to one another, so that four neighbouring codewords exceed the 64 bits the packing kernel
+    merges in registers (its two-by-two path) while no codeword exceeds its short-code limit of 27."""
+    eb = 1e-2
+    _, _, s, _ = orc.constants(eb)
+    vals = [0] + [(k + 1) // 2 * (1 if k % 2 else -1) for k in range(1, 21)]       # 0, 1, -1, 2, -2, ...
+    counts = [1 << 19] + [1 << (19 - k) for k in range(1, 20)] + [1]              # sums to 2^20
+    assert sum(counts) == 1 << 20
+    d = np.repeat(np.array(vals, np.int64), counts)
+    head = d[-40:].copy()                                        # the rarest residuals, in a row
+    rest = d[:-40]
+    np.random.default_rng(7).shuffle(rest)
+    d = np.concatenate([rest[:1000], head, rest[1000:]])
+    x = _rows_from_residuals(d, s)
+    ctx = make_ctx(gpu, sub=sub, max_numel=x.size)
+    h = check_case(gpu, orc, x, eb, ctx, orc.Config(sub=sub), stages=True)
+    assert 19 <= h["max_len"] <= 27
+
+
+@pytest.mark.parametrize("nsym,reps", [(1023, 4), (600, 7), (2, 4096), (3, 100)])
+def test_flat_histograms(gpu, orc, nsym, reps):
+    """Every residual equally often: ties at every step of the Huffman construction, so the
+    tie-break (a leaf before an internal node, each queue in its order) decides every length."""
+    eb = 1e-2
+    _, _, s, _ = orc.constants(eb)
+    half = nsym // 2
+    vals = np.concatenate([np.arange(-half, 0), np.arange(1, nsym - half + 1)]) if nsym > 3 else np.arange(nsym) - 1
+    rng = np.random.default_rng(nsym)
+    # pairs (v, -v) keep the running sums of a row small; every value and its negative occur `reps` times
+    v = np.repeat(vals, reps)
+    rng.shuffle(v)
+    d = np.stack([v, -v], axis=1).reshape(-1)
+    pad = (-d.size) % 64
+    d = np.concatenate([d, np.zeros(pad, np.int64)])
+    x = _rows_from_residuals(d, s)
+    ctx = make_ctx(gpu, sub=32, max_numel=max(x.size, 4096))
+    check_case(gpu, orc, x, eb, ctx, orc.Config(sub=32), stages=True)
+
+
 def test_nan_inf_out_of_range(gpu, orc):
     ctx = make_ctx(gpu)
     x = activation((1, 4, 40, 40), seed=3).numpy()
