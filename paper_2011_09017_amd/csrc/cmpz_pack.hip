@@ -1,16 +1,17 @@
 // Sweep 2 of compression: chunked Huffman bit-packing (the entropy-coding stage of Section 3.1)
 // for all tensors of a call, in three launches with no ordering between workgroups:
 //
-//   k_lengths  one streaming pass over the 16-bit symbols: the bit count of every sub-block
-//              (written straight into the container), of every chunk and of every range of
-//              kPackChunks chunks;
+//   k_lengths  one streaming pass over the symbols (8 or 16 bits each, as the first sweep left
+//              them): the bit count of every sub-block (written straight into the container),
+//              of every chunk and of every range of kPackChunks chunks;
 //   k_scan     one workgroup per tensor: exclusive prefix sums of the ranges' payload units
 //              and outlier counts, the container header, the decision whether it fits;
 //   k_pack     the same ranges again: chunk offsets from the range's prefix, the codewords of
-//              a chunk OR-ed into a per-wave LDS image at their own bit positions, 128-bit
-//              stores; outlier records of the chunks that hold any.
+//              a chunk (four neighbours merged in registers) OR-ed into a per-wave LDS image at
+//              their own bit positions, 128-bit stores; outlier records of the chunks that hold
+//              any.
 //
-// Reading the symbols twice costs 2 bytes per element of extra traffic and buys packing
+// Reading the symbols twice costs 1 to 2 bytes per element of extra traffic and buys packing
 // workgroups that never wait for one another: every wave walks its own chunks with no
 // workgroup barrier after the offsets are known.
 #include "cmpz_internal.h"
