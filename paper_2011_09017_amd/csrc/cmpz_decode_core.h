@@ -21,11 +21,12 @@ constexpr uint32_t kT2Size = 1u << kT2Bits;
 struct DecodeTables {
     uint16_t t1[kT1Size];
     uint16_t t2[kT2Size];
-    uint16_t sorted[kMaxSym];     // symbols ordered by (length, symbol), each as its residual
-                                  // (symbol - radius) in 10 bits, two's complement
-    uint64_t first[64];           // first canonical code of each length
-    uint32_t count[64];           // codes of each length
-    uint32_t offs[64];            // index into sorted[] of the first symbol of each length
+    uint32_t sorted3[(kMaxSym + 2) / 3];   // symbols ordered by (length, symbol), each as its residual
+                                  // (symbol - radius) in 10 bits, two's complement, three to a word
+                                  // (read only for codewords that neither table level resolves)
+    uint64_t first[kMaxCodeLen + 2];   // first canonical code of each length (indexed by the length)
+    uint32_t count[kMaxCodeLen + 2];   // codes of each length
+    uint32_t offs[kMaxCodeLen + 2];    // index into sorted[] of the first symbol of each length
     uint32_t t32;                 // left-aligned threshold above which codes are longer than kLB
     uint32_t sh;                  // level-2 shift
     uint32_t has_long;            // any code longer than kLB bits
@@ -33,6 +34,13 @@ struct DecodeTables {
     uint32_t payload_units;
     uint32_t n_outliers;
 };
+
+// Entry i of the symbols ordered by (length, symbol).
+__device__ __forceinline__ uint32_t sorted_at(const DecodeTables &T, uint32_t i)
+{
+    const uint32_t w = i / 3u;
+    return (T.sorted3[w] >> (10u * (i - 3u * w))) & 1023u;
+}
 
 // Cooperative copy global -> LDS (both are the same struct).
 __device__ __forceinline__ void load_tables(DecodeTables &dst, const DecodeTables *__restrict__ src, int tid,
@@ -45,23 +53,30 @@ __device__ __forceinline__ void load_tables(DecodeTables &dst, const DecodeTable
 }
 
 // Validation of the container header and code lengths, and construction of the decode tables
-// in LDS, by one workgroup of 256 threads (every workgroup of the fused decode kernel does this
-// for itself: about a microsecond, and no separate kernel or round trip through memory).
-// `scratch` is LDS the caller does not need yet (at least 12 KB).  Returns 0 or the status bits
-// of the defect found; contains barriers, so all 256 threads must call it.
+// in LDS, by one workgroup of NT >= 256 threads (every workgroup of the fused decode kernel does
+// this for itself: about a microsecond, and no separate kernel or round trip through memory).
+// The first 256 threads do the work (four symbols each); the others only help to fill level 1.
+// `scratch` is LDS the caller does not need yet (at least 12 KB; the ordered symbols are laid out
+// there as 16-bit values while the tables are filled).  Returns 0 or the status bits
+// of the defect found; contains barriers, so all NT threads must call it.
 //
 // Canonical codes are ascending in (length, symbol) when left-aligned, so with
 //   s[l] = count[l] << (48 - l)  and  P[l] = sum of s[j] over 1 <= j < l
 // the first code of length l is P[l] >> (48 - l), the code is complete iff the total is 2^48,
 // and a left-aligned value v belongs to the shortest length l with v < P[l+1].
-__device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const DecompressArgs &a, uint32_t *scratch)
+template <int NT>
+__device__ __forceinline__ uint32_t build_tables(DecodeTables &T, const DecompressArgs &a, uint32_t *scratch)
 {
+    static_assert(NT >= 256 && NT % 64 == 0, "whole waves, at least four");
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const bool worker = tid < 256;                                    // uniform in a wave
     Header *hd = reinterpret_cast<Header *>(scratch);                 // 64 words
     uint32_t *ends = scratch + 64;                                    // 4 words
     uint32_t *bad_s = scratch + 68, *bad2_s = scratch + 69;       // defects found before / after the second barrier
     uint64_t *lim = reinterpret_cast<uint64_t *>(scratch + 72);       // 64 x u64: P[l+1], units of 2^-48
     uint32_t (*wave_cnt)[64] = reinterpret_cast<uint32_t (*)[64]>(scratch + 200);   // 16 x 64: [pass*4 + wave][length]
+    uint16_t *sorted = reinterpret_cast<uint16_t *>(scratch + 1224);  // kMaxSym x u16
+    uint32_t *used_s = scratch + 70;
     const uint32_t nsym = 2 * a.radius;
 
     if (tid < (int)(kHeaderBytes / 4)) {
@@ -75,7 +90,7 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
         ends[k] = (k == 0) ? chunk_off[0] : (k == 1) ? chunk_off[a.lay.nchunks] : (k == 2) ? outl_off[0] : outl_off[a.lay.nchunks];
     }
     if (tid == 68) { *bad_s = 0; *bad2_s = 0; }
-    for (int k = tid; k < 16 * 64; k += 256) (&wave_cnt[0][0])[k] = 0;
+    for (int k = tid; k < 16 * 64; k += NT) (&wave_cnt[0][0])[k] = 0;
     // code lengths, 4 symbols per thread (symbol q*256 + tid), fetched while the header arrives
     const uint32_t padded = (nsym + 15u) & ~15u;
     uint32_t L[4];
@@ -84,7 +99,7 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
     for (int q = 0; q < 4; ++q) {
         const uint32_t k = q * 256u + tid;
         uint32_t v = 0;
-        if (k < padded) v = a.buf[a.lay.off_lens + k];
+        if (worker && k < padded) v = a.buf[a.lay.off_lens + k];
         if ((k >= nsym && v) || v > kMaxCodeLen) { bad_len = true; v = 0; }
         L[q] = v;
     }
@@ -171,7 +186,7 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
         const uint64_t incl = (uint64_t)i0 + ((uint64_t)i1 << 24) + ((uint64_t)i2 << 48);
         const uint64_t excl = incl - sl;
         const uint64_t first = (lane >= 1 && lane <= (int)kMaxCodeLen) ? (excl >> (kMaxCodeLen - lane)) : 0ull;
-        T.first[lane] = first; T.count[lane] = cnt; T.offs[lane] = offs;
+        if (lane <= (int)kMaxCodeLen) { T.first[lane] = first; T.count[lane] = cnt; T.offs[lane] = offs; }
         lim[lane] = incl;
         if (lane == 63) {
             uint32_t bad = 0;
@@ -182,6 +197,7 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
             if (used == 0 && a.numel != 0 && !(a.zero_blocks && hd->total_bits == 0)) bad = kStFormat;
             if (hd->max_len != max_len) bad = kStFormat;
             if (bad) *bad2_s = bad;
+            *used_s = used;
             T.max_len = max_len;
         }
         if (lane == (int)kLB) {
@@ -199,7 +215,7 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
     // symbols ordered by (length, symbol)
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-        if (L[q]) T.sorted[T.offs[L[q]] + wave_cnt[q * 4 + wv][L[q]] + in_wave[q]] = (uint16_t)((q * 256 + tid - a.radius) & 1023u);
+        if (L[q]) sorted[T.offs[L[q]] + wave_cnt[q * 4 + wv][L[q]] + in_wave[q]] = (uint16_t)((q * 256 + tid - a.radius) & 1023u);
     __syncthreads();
 
     // level 1: entry idx is the codeword (if any, of at most kLB bits) that prefixes idx
@@ -211,18 +227,18 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
             l1[l] = v > kT1Size ? kT1Size : (uint32_t)v;
         }
 #pragma unroll 2
-        for (uint32_t idx = tid; idx < kT1Size; idx += 256) {
+        for (uint32_t idx = tid; idx < kT1Size; idx += NT) {
             uint32_t l = 1;
 #pragma unroll
             for (uint32_t k = 1; k <= kLB; ++k) l += (idx >= l1[k]) ? 1u : 0u;
             uint32_t e = 0;
-            if (l <= kLB) e = T.sorted[T.offs[l] + (idx >> (kLB - l)) - (uint32_t)T.first[l]] | (l << 10);
+            if (l <= kLB) e = sorted[T.offs[l] + (idx >> (kLB - l)) - (uint32_t)T.first[l]] | (l << 10);
             T.t1[idx] = (uint16_t)e;
         }
     }
     // level 2: entry i covers left-aligned 32-bit values t32 + [i << sh, (i+1) << sh); it holds a
     // codeword only if the whole entry lies inside it (length at most 32 - sh)
-    {
+    if (worker) {
         const uint32_t sh = T.sh, t32 = T.t32, has_long = T.has_long;
         const uint32_t lmax = (32 - sh < T.max_len) ? 32 - sh : T.max_len;
         constexpr int kPer = (int)kT2Size / 256;            // entries per thread
@@ -240,8 +256,19 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
         for (int k = 0; k < kPer; ++k) {
             uint32_t e = 0;
             if (has_long && v[k] < (1ull << 32) && l[k] <= lmax)
-                e = T.sorted[T.offs[l[k]] + (uint32_t)((v[k] >> (32 - l[k])) - T.first[l[k]])] | (l[k] << 10);
+                e = sorted[T.offs[l[k]] + (uint32_t)((v[k] >> (32 - l[k])) - T.first[l[k]])] | (l[k] << 10);
             T.t2[tid + 256 * k] = (uint16_t)e;
+        }
+    }
+    // the ordered symbols in their packed form, for the codewords the two levels leave
+    {
+        const uint32_t used = *used_s;
+        for (uint32_t w = tid; w < (kMaxSym + 2) / 3; w += NT) {
+            uint32_t v = 0;
+#pragma unroll
+            for (uint32_t j = 0; j < 3; ++j)
+                if (3 * w + j < used) v |= (uint32_t)sorted[3 * w + j] << (10 * j);
+            T.sorted3[w] = v;
         }
     }
     __syncthreads();
@@ -252,6 +279,15 @@ __device__ __forceinline__ uint32_t build_tables_256(DecodeTables &T, const Deco
 __device__ __forceinline__ int32_t entry_residual(uint32_t e)
 {
     return __builtin_amdgcn_sbfe((int)e, 0, 10);
+}
+
+// Level 2 resolves every codeword of at most 32 - sh bits (its entries start at t32, a multiple
+// of 2^sh whenever such a codeword exists, so each one covers whole entries): the search over
+// the lengths starts behind them.
+__device__ __forceinline__ uint32_t first_unresolved_length(uint32_t sh)
+{
+    const uint32_t l = 33u - sh;
+    return l > kLB + 1 ? l : kLB + 1;
 }
 
 // Decode `count` codewords that start at bit `start` of a chunk stream whose 32-bit words
@@ -305,10 +341,10 @@ __device__ __forceinline__ uint32_t decode_run(const DecodeTables &T, RD rd, uin
                 uint64_t w64 = ((((uint64_t)rd(w0)) << 32) | rd(w0 + 1)) << off;
                 if (off) w64 |= (uint64_t)(rd(w0 + 2) >> (32 - off));
                 uint32_t len = 0, sy = 0;                    // no match: residual 0
-                for (uint32_t L = kLB + 1; L <= T.max_len; ++L) {
+                for (uint32_t L = has_long ? first_unresolved_length(sh) : kLB + 1; L <= T.max_len; ++L) {
                     const uint64_t code = w64 >> (64 - L);
                     if (code >= T.first[L] && code - T.first[L] < T.count[L]) {
-                        sy = T.sorted[T.offs[L] + (uint32_t)(code - T.first[L])];
+                        sy = sorted_at(T, T.offs[L] + (uint32_t)(code - T.first[L]));
                         len = L;
                         break;
                     }
@@ -371,14 +407,14 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
                 e = T.t2[i2];
             }
             if (__builtin_expect(e == 0, 0)) {
-                // canonical search over the longer lengths on a 64-bit window
+                // canonical search over the lengths the second level does not resolve, on a 64-bit window
                 const uint32_t lo = __builtin_amdgcn_alignbit(wb, wc, npos);
                 const uint64_t v = (((uint64_t)hi) << 32) | lo;
                 uint32_t len = 0, sy = 0;                     // no match: residual 0
-                for (uint32_t L = kLB + 1; L <= T.max_len; ++L) {
+                for (uint32_t L = first_unresolved_length(sh); L <= T.max_len; ++L) {
                     const uint64_t code = v >> (64 - L);
                     if (code >= T.first[L] && code - T.first[L] < T.count[L]) {
-                        sy = T.sorted[T.offs[L] + (uint32_t)(code - T.first[L])];
+                        sy = sorted_at(T, T.offs[L] + (uint32_t)(code - T.first[L]));
                         len = L;
                         break;
                     }

@@ -78,7 +78,7 @@ struct Stage {
 // container and builds that codebook's decode tables for itself, about a microsecond), its waves
 // take every item_stride-th item of the tensor.
 template <int SUB>
-__global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
+__global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
 {
     using RT = int16_t;
     constexpr int kRows = 8;                              // rows of the column pass in flight together
@@ -90,12 +90,24 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
     static_assert(2 * kND <= kStageWords, "the lane records live in the staging buffer");
     static_assert(kStageWords / 4 == 2 * kWave, "two units per lane");
 
-    __shared__ DecodeTables T;
-    __shared__ RT       Rs[kWaves][kBandMax + kND];       // one pad slot per sub-block: lane-conflict free
-    __shared__ uint32_t Ps[kWaves][kE * kWave + 2];       // exclusive prefix of sub-block bit counts
-    __shared__ __align__(16) uint32_t Ss[kWaves][kStagePad + kStageWords + stage_tail_words(SUB)];   // staged payload and the words a damaged
-                                                                           // stream may read past it; after the decode, the lane records
-    static_assert(sizeof(Rs) >= 13 * 1024, "the table build borrows Rs as scratch");
+    // One struct, so that the order in LDS is fixed: the words a damaged stream may read past a
+    // wave's staged payload (stage_tail_words) are the next wave's, and behind the last wave's
+    // lie the tables.  32 KB at most: five workgroups share a compute unit's LDS.
+    struct Lds {
+        RT Rs[kWaves][kBandMax + kND];                    // one pad slot per sub-block: lane-conflict free
+        alignas(16) uint32_t Ss[kStagePad + kWaves * kStageWords];   // per wave: staged payload; after the decode, the lane records
+        DecodeTables T;
+    };
+    __shared__ Lds lds;
+    static_assert(sizeof(Lds) <= 32 * 1024, "five workgroups per compute unit");
+    static_assert(sizeof(lds.Rs) >= 13 * 1024, "the table build borrows Rs as scratch");
+    static_assert(sizeof(DecodeTables) >= 4 * stage_tail_words(SUB), "reads past the last wave's payload stay inside the tables");
+    DecodeTables &T = lds.T;
+    // the exclusive prefix of a band's sub-block bit counts lives in the staging buffer too, behind
+    // the lane records: it is written after a band's decode and read (into registers) before the
+    // next band's payload is stored over it; a wave's LDS operations stay in order
+    constexpr int kPOff = kStagePad + 2 * kND;
+    static_assert(kPOff + kE * kWave + 2 <= kStagePad + kStageWords, "lane records and prefix fit the staging buffer");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);     // tells the compiler that it is uniform in the wave
@@ -114,19 +126,19 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_fused(BatchD b)
     }
     // every workgroup validates the container and builds the decode tables for itself
     {
-        const uint32_t defect = build_tables_256(T, a, reinterpret_cast<uint32_t *>(&Rs[0][0]));
+        const uint32_t defect = build_tables<kThreads>(T, a, reinterpret_cast<uint32_t *>(&lds.Rs[0][0]));
         if (defect) {
             if (blockIdx.x == td.wg_base && tid == 0) atomicOr(a.status, defect);
             return;
         }
     }
     // ---- from here on the waves are on their own ----
-    RT       *R = Rs[wv];
-    uint32_t *P = Ps[wv];
-    uint32_t *S = Ss[wv];
+    RT       *R = lds.Rs[wv];
+    uint32_t *S = lds.Ss + wv * kStageWords;             // the wave's payload starts at S + kStagePad
+    uint32_t *P = S + kPOff;
     // per decode lane, after the decode: .x = offset of the lane's first row start (elements before
     // it lack the carry), .y = the carry
-    uint2 *RC = reinterpret_cast<uint2 *>(S);
+    uint2 *RC = reinterpret_cast<uint2 *>(S + kStagePad);
     const uint32_t payload_units = T.payload_units, n_outl = T.n_outliers;
 
     const uint32_t W = a.W, H = a.H, HW = a.HW;
@@ -510,8 +522,8 @@ void launch_decode_fused(BatchD &b, uint32_t cus, Profiler *prof, hipStream_t st
 {
     uint64_t total = 0;
     for (uint32_t k = 0; k < b.n; ++k) if (b.t[k].nitems) total += b.t[k].numel;
-    const uint64_t slots = 4ull * cus;
-    uint64_t rounds = total / (slots * 65536ull);            // at least 64 K elements per workgroup and round
+    const uint64_t slots = 5ull * cus;
+    uint64_t rounds = total / (slots * 16384ull * kWaves);   // at least 16 K elements per wave and round
     rounds = rounds < 1 ? 1 : rounds > 6 ? 6 : rounds;
     const uint64_t deal = slots * rounds;
     uint32_t grid = 0;

@@ -22,9 +22,9 @@ constexpr int      kDecThreads = 128;              // sub-blocks (lanes) per dec
 __global__ __launch_bounds__(256) void k_decode_tables(DecompressArgs a, DecodeTables *tb)
 {
     __shared__ DecodeTables T;
-    __shared__ uint32_t scratch[3584];               // 14 KB, what build_tables_256 asks for
+    __shared__ uint32_t scratch[3584];               // 14 KB, what build_tables asks for
     const int tid = threadIdx.x;
-    const uint32_t defect = build_tables_256(T, a, scratch);
+    const uint32_t defect = build_tables<256>(T, a, scratch);
     if (defect) {
         if (tid == 0) { a.meta[kMetaBad] = 1; atomicOr(a.status, defect); }
         return;

@@ -237,7 +237,7 @@ __host__ __device__ inline DecompressArgs decompress_args(const BatchD &b, const
     return a;
 }
 
-constexpr uint32_t kLB = 12;                      // bits resolved by the first decode table (8 KB of LDS; with the
+constexpr uint32_t kLB = 11;                      // bits resolved by the first decode table (8 KB of LDS; with the
                                                   // fused decoder's other arrays four workgroups just fit a CU)
 struct DecodeTables;                              // cmpz_decode_core.h
 
