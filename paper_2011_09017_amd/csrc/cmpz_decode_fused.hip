@@ -81,7 +81,7 @@ template <int SUB>
 __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
 {
     using RT = int16_t;
-    constexpr int kRows = 8;                              // rows of the column pass in flight together
+    constexpr int kRows = 4;                              // rows of the column pass in flight together
     constexpr int kLog  = Cfg<SUB>::kLog;
     constexpr int kND   = kBandMax / SUB;                 // decode lanes per band
     constexpr int kNSub = (int)kChunk / SUB;              // sub-blocks per chunk
