@@ -48,7 +48,8 @@ template <> struct Cfg<64>  { static constexpr int kLog = 6; };
 template <> struct Cfg<32>  { static constexpr int kLog = 5; };
 
 struct FusedPlan {
-    uint32_t big;          // 0: groups of whole planes; 1: one plane per item, bands of rows
+    uint32_t big;          // 0: groups of whole planes; 1: one plane per item, bands of rows; 2: the same,
+                           // the four waves of a workgroup on four consecutive bands of one plane
     uint32_t G;            // planes per group (big == 0)
     uint32_t Rb;           // rows per band (big == 1)
     uint32_t nitems;
@@ -77,7 +78,8 @@ struct Stage {
 // One launch decodes all tensors of a call: a workgroup belongs to one tensor (it validates that
 // container and builds that codebook's decode tables for itself, about a microsecond), its waves
 // take every item_stride-th item of the tensor.
-template <int SUB>
+// COOP: the variant for few large planes (plan value big == 2), a launch of its own.
+template <int SUB, bool COOP>
 __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
 {
     using RT = int16_t;
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
     const uint32_t vzero = __builtin_amdgcn_mbcnt_lo(0u, 0u);    // 0, but not known to be uniform
     auto band_of = [&](uint32_t item, uint32_t b) -> Band {
         Band g;
-        g.valid = item < pl.nitems;
+        g.valid = item < pl.nitems && (!pl.big || b * pl.Rb < H);
         if (!g.valid) { g.e0 = g.n = g.rows = g.plane0 = g.npl = g.row0 = 0; return g; }
         if (pl.big) {
             g.plane0 = item; g.npl = 1; g.row0 = b * pl.Rb;
@@ -238,10 +240,17 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
         if ((uint32_t)lane + kWave < st.nq) s1 = payload4[(uint64_t)st.q0 + lane + kWave];
     };
 
+    // Few large planes (fewer than the chip has room for waves): the four waves of a workgroup take
+    // four consecutive bands of the same plane, decode them side by side, and then share the column
+    // pass by columns, each wave running its quarter of the columns down all four bands, with two
+    // workgroup barriers per round.  `bi` then counts rounds of four bands.
+    constexpr bool coop = COOP;
     const uint32_t nbands_big = pl.big ? (H + pl.Rb - 1) / pl.Rb : 1u;
-    const uint32_t item_stride = td.nwg * kWaves;
-    uint32_t item = (blockIdx.x - td.wg_base) * kWaves + wv, bi = 0;
-    Band cur = band_of(item, bi);
+    const uint32_t nsteps = coop ? (nbands_big + kWaves - 1) / kWaves : nbands_big;
+    const uint32_t item_stride = coop ? td.nwg : td.nwg * kWaves;
+    uint32_t item = coop ? blockIdx.x - td.wg_base : (blockIdx.x - td.wg_base) * kWaves + wv, bi = 0;
+    auto band_at = [&](uint32_t it, uint32_t step) -> Band { return band_of(it, coop ? step * kWaves + wv : step); };
+    Band cur = band_at(item, bi);
     Ahead fa = fetch(cur);
     int32_t colacc[kColGroups] = {0, 0, 0, 0};               // running column sums (big planes)
     uint4 s0 = make_uint4(0, 0, 0, 0), s1 = s0;
@@ -252,17 +261,18 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
         stage_load(sg, s0, s1);
     }
 
-    while (cur.valid) {
+    while (item < pl.nitems) {                       // uniform in the wave; with shared planes, in the workgroup
         // ---- next band: geometry now, bit counts in flight while this band is decoded ----
         uint32_t nitem = item, nb = bi + 1;
-        if (nb >= nbands_big) { nitem = item + item_stride; nb = 0; }
-        const Band nxt = band_of(nitem, nb);
+        if (nb >= nsteps) { nitem = item + item_stride; nb = 0; }
+        const Band nxt = band_at(nitem, nb);
         const Ahead fn = fetch(nxt);
 
         const uint32_t e0 = cur.e0, n = cur.n, rows = cur.rows, npl = cur.npl;
         const uint32_t sb0 = e0 >> kLog;
-        const uint32_t sb1 = (e0 + n - 1) >> kLog;
-        const uint32_t nsb = sb1 - sb0 + 1;              // <= kND by construction of the plan
+        // (a wave without a band in this round of a shared plane: no sub-blocks, no rows)
+        const uint32_t sb1 = cur.valid ? (e0 + n - 1) >> kLog : sb0;
+        const uint32_t nsb = cur.valid ? sb1 - sb0 + 1 : 0u;   // <= kND by construction of the plan
         const uint32_t base = sb0 << kLog;
         const uint32_t u0 = e0 - base;
         const uint32_t j0 = sb0 & (kNSub - 1);           // position of sb0 in its chunk
@@ -427,13 +437,18 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
 
         // ---- column prefix sums (adding the lanes' carries), de-quantisation, stores: one lane per column ----
         const uint32_t nrow = pl.big ? rows : H;
-        // byte offsets from the band's first output element: the stores then take a uniform base
-        // and a 32-bit offset per lane
-        char *__restrict__ band_out = reinterpret_cast<char *>(a.xout + e0);
-        auto walk = [&](uint32_t col, int32_t acc) -> int32_t {
+        // One column of a band (Rj: its sums along the rows, RCj: its lane records, first element
+        // uj0 slots into Rj, nrowj rows, output from outj on), continuing the column sum acc.
+        // Byte offsets from the band's first output element: the stores then take a uniform base
+        // and a 32-bit offset per lane.
+        auto walk_band = [&](const RT *Rj, const uint2 *RCj, uint32_t uj0, uint32_t nrowj, char *__restrict__ band_out,
+                             uint32_t col, int32_t acc) -> int32_t {
+            const RT *R = Rj;
+            const uint2 *RC = RCj;
+            const uint32_t nrow = nrowj;
             const uint32_t p = pl.big ? 0u : pl.divW.div(col);
             const uint32_t w = col - p * W;
-            uint32_t u = p * HW + w + u0;
+            uint32_t u = p * HW + w + uj0;
             uint32_t off = (p * HW + w) * 4u;
             // kRows rows at a time, their loads in flight together; then the short batch that may remain
             auto batch = [&](auto full_c, uint32_t nr) {
@@ -469,17 +484,41 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
             if (h < nrow) batch(std::false_type{}, nrow - h);        // uniform
             return acc;
         };
-        if (pl.big) {
-#pragma unroll
-            for (int c = 0; c < kColGroups; ++c) {
-                const uint32_t col = c * kWave + lane;
-                if (col < W) colacc[c] = walk(col, colacc[c]);
+        auto walk = [&](uint32_t col, int32_t acc) -> int32_t {
+            return walk_band(R, RC, u0, nrow, reinterpret_cast<char *>(a.xout + e0), col, acc);
+        };
+        if (coop) {
+            // every wave has decoded its band of this round: now a quarter of the columns each,
+            // down the round's bands in their order
+            __syncthreads();
+            const uint32_t cw = (W + kWaves - 1) / kWaves;           // <= 64: W <= kColGroups * 64
+            const uint32_t col = (uint32_t)wv * cw + (uint32_t)lane;
+            if ((uint32_t)lane < cw && col < W) {
+                int32_t acc = colacc[0];
+                for (uint32_t j = 0; j < (uint32_t)kWaves; ++j) {
+                    const uint32_t row0 = (bi * kWaves + j) * pl.Rb;
+                    if (row0 >= H) break;                            // uniform
+                    const uint32_t rowsj = (H - row0 < pl.Rb) ? H - row0 : pl.Rb;
+                    const uint32_t ej0 = item * HW + row0 * W;
+                    acc = walk_band(lds.Rs[j], reinterpret_cast<const uint2 *>(lds.Ss + j * kStageWords + kStagePad),
+                                    ej0 - ((ej0 >> kLog) << kLog), rowsj, reinterpret_cast<char *>(a.xout + ej0), col, acc);
+                }
+                colacc[0] = acc;
             }
+            __syncthreads();                              // R and the staging buffers are reused by the next round
         } else {
-            const uint32_t ncols = npl * W;
-            for (uint32_t col = lane; col < ncols; col += kWave) (void)walk(col, 0);
+            if (pl.big) {
+#pragma unroll
+                for (int c = 0; c < kColGroups; ++c) {
+                    const uint32_t col = c * kWave + lane;
+                    if (col < W) colacc[c] = walk(col, colacc[c]);
+                }
+            } else {
+                const uint32_t ncols = npl * W;
+                for (uint32_t col = lane; col < ncols; col += kWave) (void)walk(col, 0);
+            }
+            wave_sync();                                      // R and the staging buffer are reused by the next band
         }
-        wave_sync();                                      // R and the staging buffer are reused by the next band
         cur = nxt; fa = fn; sg = sgn; item = nitem; bi = nb;
     }
     if (bad) atomicOr(a.status, kStFormat);
@@ -510,14 +549,15 @@ bool plan_decode_fused(TensorD *t, uint32_t sub)
     return true;
 }
 
-// One launch over the tensors of the group that have a plan.  Four workgroups are resident per
-// compute unit.  A small call gets one round of them (a second round would build its decode tables
-// for little work); a large one up to six rounds, dealt to the tensors in proportion to their
-// elements, so that workgroups of different cost (small planes cost more per element than large
-// ones) even out and the chip does not idle while the last round's slowest workgroup finishes.
-// Measured on the ResNet-18-shaped stream (17 tensors, 591 M elements): 1.45 / 1.16 / 1.03 / 1.02 /
-// 1.05 / 1.23 ms for 1 / 2 / 4 / 6 / 16 / 64 rounds; single tensors of 37 M and 51 M elements: one
-// round 7 % faster than two.  No more than a tensor has items for, at least one.
+// One launch over the tensors of the group that have a plan (and a second one, of the variant
+// that shares planes between waves, over those with few large planes).  Five workgroups are
+// resident per compute unit.  A small call gets one round of them (a second round would build its
+// decode tables for little work); a large one up to six rounds, dealt to the tensors in proportion
+// to their elements, so that workgroups of different cost (small planes cost more per element than
+// large ones) even out and the chip does not idle while the last round's slowest workgroup
+// finishes.  Measured on the ResNet-18-shaped stream (17 tensors, 591 M elements): 1.00 / 0.96 /
+// 0.93 / 0.94 / 0.94 / 0.94 ms for 3 / 4 / 5 / 6 / 8 / 12 rounds.  No more than a tensor has items
+// for, at least one.
 void launch_decode_fused(BatchD &b, uint32_t cus, Profiler *prof, hipStream_t st)
 {
     uint64_t total = 0;
@@ -526,23 +566,39 @@ void launch_decode_fused(BatchD &b, uint32_t cus, Profiler *prof, hipStream_t st
     uint64_t rounds = total / (slots * 16384ull * kWaves);   // at least 16 K elements per wave and round
     rounds = rounds < 1 ? 1 : rounds > 6 ? 6 : rounds;
     const uint64_t deal = slots * rounds;
-    uint32_t grid = 0;
     for (uint32_t k = 0; k < b.n; ++k) {
         TensorD &t = b.t[k];
-        t.wg_base = grid;
-        t.nwg = 0;
-        if (!t.nitems) continue;
-        const uint64_t share = ((uint64_t)t.numel * deal + total - 1) / total;
-        const uint64_t most = (t.nitems + kWaves - 1) / kWaves;
-        t.nwg = (uint32_t)(share < most ? share : most);
-        if (t.nwg < 1) t.nwg = 1;
-        grid += t.nwg;
+        // Large planes, fewer of them than the chip holds waves (one wave per plane would leave it
+        // half empty): a workgroup per plane, its waves side by side on the plane's bands.
+        if (t.nitems && t.big) t.big = (t.nitems < slots * kWaves && t.shape[2] > t.Rb) ? 2u : 1u;
     }
-    if (!grid) return;
-    switch (b.sub) {
-    case 32:  launch(prof, kKDecodeFused, k_decode_fused<32>, dim3(grid), dim3(kThreads), st, b); break;
-    case 64:  launch(prof, kKDecodeFused, k_decode_fused<64>, dim3(grid), dim3(kThreads), st, b); break;
-    default:  launch(prof, kKDecodeFused, k_decode_fused<128>, dim3(grid), dim3(kThreads), st, b); break;
+    for (uint32_t shared = 0; shared < 2; ++shared) {
+        uint32_t grid = 0;
+        for (uint32_t k = 0; k < b.n; ++k) {
+            TensorD &t = b.t[k];
+            t.wg_base = grid;
+            t.nwg = 0;
+            if (!t.nitems || (t.big == 2) != (shared == 1)) continue;    // not in this launch: no workgroups
+            const uint64_t share = ((uint64_t)t.numel * deal + total - 1) / total;
+            const uint64_t most = shared ? t.nitems : (t.nitems + kWaves - 1) / kWaves;
+            t.nwg = (uint32_t)(share < most ? share : most);
+            if (t.nwg < 1) t.nwg = 1;
+            grid += t.nwg;
+        }
+        if (!grid) continue;
+        if (shared) {
+            switch (b.sub) {
+            case 32:  launch(prof, kKDecodeFused, k_decode_fused<32, true>, dim3(grid), dim3(kThreads), st, b); break;
+            case 64:  launch(prof, kKDecodeFused, k_decode_fused<64, true>, dim3(grid), dim3(kThreads), st, b); break;
+            default:  launch(prof, kKDecodeFused, k_decode_fused<128, true>, dim3(grid), dim3(kThreads), st, b); break;
+            }
+        } else {
+            switch (b.sub) {
+            case 32:  launch(prof, kKDecodeFused, k_decode_fused<32, false>, dim3(grid), dim3(kThreads), st, b); break;
+            case 64:  launch(prof, kKDecodeFused, k_decode_fused<64, false>, dim3(grid), dim3(kThreads), st, b); break;
+            default:  launch(prof, kKDecodeFused, k_decode_fused<128, false>, dim3(grid), dim3(kThreads), st, b); break;
+            }
+        }
     }
 }
 

@@ -118,6 +118,20 @@ def test_band_and_group_shapes(gpu, orc, sub, shape):
     check_case(gpu, orc, x, 1e-2, ctx, orc.Config(sub=sub))
 
 
+@pytest.mark.parametrize("shape,sub", [((23, 230, 45, 47), 32), ((23, 230, 45, 47), 128), ((11, 500, 70, 33), 32)])
+def test_many_large_planes(gpu, orc, shape, sub):
+    """Planes larger than one band, and more of them than the chip holds waves: every wave walks
+    its own planes band by band (with fewer planes, as in the cases above, the four waves of a
+    workgroup share a plane).  Odd sizes: the last band of a plane is short."""
+    ctx = make_ctx(gpu, sub=sub, max_numel=int(np.prod(shape)))
+    x = activation(shape, 5, 0.5, seed=sub + shape[3]).numpy()
+    rng = np.random.default_rng(shape[2])
+    for _ in range(40):                                      # a few planes with outliers
+        x[rng.integers(shape[0]), rng.integers(shape[1]), rng.integers(shape[2]), rng.integers(shape[3])] = 300.0
+    h = check_case(gpu, orc, x, 1e-2, ctx, orc.Config(sub=sub))
+    assert h["n_outliers"] > 0
+
+
 @pytest.mark.parametrize("sub", [32, 64])
 def test_items_with_and_without_outliers(gpu, orc, sub):
     """The fast decode kernel hands the planes (or groups of small planes) whose chunks hold
