@@ -394,6 +394,9 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
     // one arithmetic shift of npos
     int32_t N = (int32_t)npos >> 5;
     const uint32_t *Sw = S + kStagePad;
+    // LDS byte address of stream word 1: word 1 - Nn is then one multiply-add away
+    typedef const uint32_t __attribute__((address_space(3))) *lds_word_ptr;
+    const uint32_t sw1 = (uint32_t)(uintptr_t)(lds_word_ptr)(Sw + 1);
     uint32_t wa = Sw[-1 - N], wb = Sw[-N], wc = Sw[1 - N];
 #pragma unroll 4
     for (uint32_t k = 0; k < count; ++k) {
@@ -407,16 +410,30 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
                 e = T.t2[i2];
             }
             if (__builtin_expect(e == 0, 0)) {
-                // canonical search over the lengths the second level does not resolve, on a 64-bit window
-                const uint32_t lo = __builtin_amdgcn_alignbit(wb, wc, npos);
-                const uint64_t v = (((uint64_t)hi) << 32) | lo;
+                // canonical search over the lengths the second level does not resolve: up to 31 bits
+                // in 32-bit arithmetic (a code below the first one of its length wraps to a difference
+                // of at least 2^31, far above any count), beyond that on a 64-bit window
                 uint32_t len = 0, sy = 0;                     // no match: residual 0
-                for (uint32_t L = first_unresolved_length(sh); L <= T.max_len; ++L) {
-                    const uint64_t code = v >> (64 - L);
-                    if (code >= T.first[L] && code - T.first[L] < T.count[L]) {
-                        sy = sorted_at(T, T.offs[L] + (uint32_t)(code - T.first[L]));
+                const uint32_t max_len = T.max_len;
+                uint32_t L = first_unresolved_length(sh);
+                for (; L <= max_len && L < 32u; ++L) {
+                    const uint32_t rel = (hi >> (32u - L)) - (uint32_t)T.first[L];
+                    if (rel < T.count[L]) {
+                        sy = sorted_at(T, T.offs[L] + rel);
                         len = L;
                         break;
+                    }
+                }
+                if (len == 0 && max_len >= 32u) {
+                    const uint32_t lo = __builtin_amdgcn_alignbit(wb, wc, npos);
+                    const uint64_t v = (((uint64_t)hi) << 32) | lo;
+                    for (L = L < 32u ? 32u : L; L <= max_len; ++L) {
+                        const uint64_t code = v >> (64 - L);
+                        if (code >= T.first[L] && code - T.first[L] < T.count[L]) {
+                            sy = sorted_at(T, T.offs[L] + (uint32_t)(code - T.first[L]));
+                            len = L;
+                            break;
+                        }
                     }
                 }
                 if (len == 0) { bad = true; len = 1; }
@@ -431,7 +448,11 @@ __device__ __forceinline__ uint32_t decode_lds(const DecodeTables &T, const uint
         const bool moved = Nn != N;
         wa = moved ? wb : wa;
         wb = moved ? wc : wb;
-        wc = Sw[1 - Nn];
+        {
+            uint32_t at;                                     // sw1 - 4 * Nn (|Nn| is a word index: far inside 24 bits)
+            asm("v_mad_i32_i24 %0, %1, -4, %2" : "=v"(at) : "v"(Nn), "s"(sw1));
+            wc = *(lds_word_ptr)(uintptr_t)at;
+        }
         N = Nn;
         if (k >= skip) put(k, entry_residual(e));
     }

@@ -154,13 +154,13 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
     const float s = a.s;
     bool bad = false;
 
-    // What a lane fetches ahead for a band: its bit-count entries, its sub-block's chunk bounds,
-    // and (uniform) the band's range in the outlier list and the payload bounds of its chunks.
+    // What a lane fetches ahead for a band: its bit-count entries, its sub-block's chunk bounds
+    // (those of the first and the last lane are the payload bounds of the band's chunks), and, in
+    // lanes 0 and 1, the two ends of the band's range in the outlier list.
     struct Ahead {
-        uint32_t v[kE], uu0, uu1, olo, ohi, cf, cl, cl1;
+        uint32_t v[kE], uu0, uu1, oo;
     };
 
-    const uint32_t vzero = __builtin_amdgcn_mbcnt_lo(0u, 0u);    // 0, but not known to be uniform
     auto band_of = [&](uint32_t item, uint32_t b) -> Band {
         Band g;
         g.valid = item < pl.nitems && (!pl.big || b * pl.Rb < H);
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
         Ahead f;
 #pragma unroll
         for (int i = 0; i < kE; ++i) f.v[i] = 0;
-        f.uu0 = f.uu1 = f.olo = f.ohi = f.cf = f.cl = f.cl1 = 0;
+        f.uu0 = f.uu1 = f.oo = 0;
         if (!g.valid) return f;
         const uint32_t sb0 = g.e0 >> kLog, sb1 = (g.e0 + g.n - 1) >> kLog;
         const uint32_t j0 = sb0 & (kNSub - 1), ent0 = sb0 - j0, nent = j0 + (sb1 - sb0 + 1);
@@ -194,13 +194,9 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
             const uint32_t c = (sb0 + lane) / kNSub;
             f.uu0 = chunk_off[c]; f.uu1 = chunk_off[c + 1];
         }
-        // uniform values, but fetched with vector loads: scalar loads share their counter with LDS
+        // uniform values, but fetched with a vector load: scalar loads share their counter with LDS
         // traffic and return out of order, so waiting for one would drain every LDS access in flight
-        f.olo = outl_off[g.e0 / kChunk + vzero];
-        f.ohi = outl_off[(g.e0 + g.n - 1) / kChunk + 1 + vzero];
-        f.cf = chunk_off[sb0 / kNSub + vzero];
-        f.cl = chunk_off[sb1 / kNSub + vzero];
-        f.cl1 = chunk_off[sb1 / kNSub + 1 + vzero];
+        if (lane < 2) f.oo = outl_off[lane == 0 ? g.e0 / kChunk : (g.e0 + g.n - 1) / kChunk + 1];
         return f;
     };
     // exclusive prefix of a band's bit counts from the start of its first chunk
@@ -224,8 +220,10 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
         const uint32_t j0 = sb0 & (kNSub - 1), jl = sb1 & (kNSub - 1), idxl = j0 + (sb1 - sb0);
         const uint32_t first_bit = P[j0] - P[0];                 // in the first chunk's stream
         const uint32_t end_bit = P[idxl + 1] - P[idxl - jl];     // in the last chunk's stream
-        const uint32_t cf = __builtin_amdgcn_readfirstlane(f.cf), cl = __builtin_amdgcn_readfirstlane(f.cl),
-                       cl1 = __builtin_amdgcn_readfirstlane(f.cl1);
+        // the band's first sub-block is lane 0's, its last one lane (sb1 - sb0)'s
+        const uint32_t cf = __builtin_amdgcn_readfirstlane(f.uu0);
+        const uint32_t cl = (uint32_t)__builtin_amdgcn_readlane((int)f.uu0, (int)(sb1 - sb0)),
+                       cl1 = (uint32_t)__builtin_amdgcn_readlane((int)f.uu1, (int)(sb1 - sb0));
         if (!(cf <= cl && cl <= cl1 && cl1 <= payload_units)) return st;
         const uint64_t w_lo = (uint64_t)cf * 4 + (first_bit >> 5);
         const uint64_t w_hi = (uint64_t)cl * 4 + ((uint64_t)end_bit + 31) / 32;
@@ -297,7 +295,7 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
         wave_sync();
 
         // outliers of the band: a range of the outlier list (filtered by index below)
-        uint32_t olo = __builtin_amdgcn_readfirstlane(fa.olo), ohi = __builtin_amdgcn_readfirstlane(fa.ohi);
+        uint32_t olo = __builtin_amdgcn_readfirstlane(fa.oo), ohi = (uint32_t)__builtin_amdgcn_readlane((int)fa.oo, 1);
         if (olo > ohi || ohi > n_outl) { bad = true; olo = ohi = 0; }
         // uniform: no outliers, rows are summed while decoding
         const bool folded = olo == ohi;
