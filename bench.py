@@ -61,10 +61,10 @@ MEASURED_TRAFFIC = {
     ("cfg5_resnet18_stream", 32, 1e-2): {
         "profile": "profiles/hbm_traffic_cfg5_resnet18_stream.txt",
         "per_elem": {
-            "k_quant_lorenzo_split_hist": 4.0182 + 1.0508,     # 8-bit symbols in the scratch
+            "k_quant_lorenzo_split_hist": 4.0178 + 1.0509,     # 8-bit symbols in the scratch
             "k_lengths": 1.0088 + 0.0672,
-            "k_pack": 1.0138 + 0.6639,
-            "k_decode_fused": 0.8356 + 4.0196,
+            "k_pack": 1.0146 + 0.6639,
+            "k_decode_fused": 0.8339 + 4.0086,
         },
     },
 }
