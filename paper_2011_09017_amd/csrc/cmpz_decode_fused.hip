@@ -25,8 +25,8 @@
 // row prefix sum up to a per-lane carry; one segmented scan over the lanes'
 // totals yields the carries, and the column pass (one lane per column, eight
 // rows in flight) adds them on the fly, de-quantises and stores.  A band with
-// outliers stores plain residuals, patches the outliers in and runs an explicit
-// row scan.
+// outliers stores plain residuals and patches the outliers in; then its lanes
+// sum their rows in LDS, and the rest is the same.
 // Software pipeline: the bit counts of the next band are fetched during the
 // decode of the current one, and its payload during the column pass.
 #include "cmpz_decode_core.h"
@@ -303,6 +303,8 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
         // ---- decode: one lane per sub-block ----
         int32_t my_tail = 0;
         uint32_t my_reset = 0;
+        // (a band with outliers: what the lane needs to sum its rows once the outliers are patched in)
+        uint32_t late_klo = 0, late_khi = 0, late_w = 0;
         if (lane < (int)nsb) {
             const uint32_t g = sb0 + lane;
             const uint32_t uu0 = fa.uu0, uu1 = fa.uu1;
@@ -329,11 +331,9 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
             uint32_t end = 0;
             if (!lbad) {
                 // row starts among the lane's elements from klo on (the band begins at one)
+                const uint32_t l_first = el0 + klo - e0;                 // band-local index of the first element
                 uint32_t w_first = 0;
-                if (folded) {
-                    const uint32_t l_first = el0 + klo - e0;             // band-local index of the first element
-                    w_first = l_first - pl.divW.div(l_first) * W;
-                }
+                if (folded) w_first = l_first - pl.divW.div(l_first) * W;
                 const uint32_t last = nw - 1;
                 const uint32_t *__restrict__ gw =
                     reinterpret_cast<const uint32_t *>(a.buf + a.lay.off_payload + (uint64_t)uu0 * 16);
@@ -381,6 +381,7 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
                     const bool whole = (SUB == 32 && n_here == 32u);
                     end = run_decode(whole ? 32u : khi, whole ? 0u : klo,
                                      [&](uint32_t k, int32_t d) { my[k] = d; });
+                    late_klo = klo; late_khi = khi; late_w = l_first;
                 }
             }
             // a sub-block decoded to its end must land exactly on its stored bit count
@@ -389,18 +390,9 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
         }
         wave_sync();                                     // S is free: the lane records take its place
 
-        if (folded) {
-            // ---- carries: what each lane's leading elements (before its first row start) lack ----
-            int32_t v = my_tail;                                        // 0 in lanes without a sub-block
-            uint32_t f = (lane < (int)nsb && my_reset != (uint32_t)SUB) ? 1u : 0u;   // the lane's run contains a row start
-            wave_segmented_sum(v, f);                                   // v: row-sum at the end of the lane's run
-            // what flows into a lane is the inclusive value of the lane before it; a band begins a row
-            int32_t into = (int32_t)dpp_u32<0x138, 0xf>((uint32_t)v);   // wave_shr:1
-            if (lane == 0) into = 0;
-            if (lane < kND) RC[lane] = make_uint2(lane < (int)nsb ? my_reset : 0u, (uint32_t)into);
-        } else {
-            if (lane < kND) RC[lane] = make_uint2(0u, 0u);
-            // ---- outliers overwrite their residuals, then an explicit row scan ----
+        if (!folded) {
+            // ---- outliers overwrite their residuals; then every lane sums its rows as the other
+            //      bands' lanes do while they decode ----
             for (uint32_t k = olo + lane; k < ohi; k += kWave) {
                 const uint32_t i = oidx[k];
                 if (i >= e0 && i - e0 < n) {
@@ -409,19 +401,30 @@ __global__ __launch_bounds__(kThreads, 5) void k_decode_fused(BatchD b)
                 }
             }
             wave_sync();
-            int32_t carry = 0;
-            for (uint32_t l0 = 0; l0 < n; l0 += kWave) {
-                const uint32_t l = l0 + lane;
-                const bool in = l < n;
-                const uint32_t u = l + u0;
-                const uint32_t ph = u + (u >> kLog);
-                int32_t v = in ? R[ph] : 0;
-                uint32_t f = (l - pl.divW.div(l) * W == 0) ? 1u : 0u;      // row start
-                wave_segmented_sum(v, f);
-                if (!f) v += carry;
-                if (in) R[ph] = v;
-                carry = __builtin_amdgcn_readlane(v, 63);
+            if (late_klo < late_khi) {
+                RT *my = R + lane * (SUB + 1);
+                uint32_t w = late_w - pl.divW.div(late_w) * W;           // place in its row of the lane's first element
+                int32_t run = 0;
+                uint32_t first_reset = (uint32_t)SUB;
+                for (uint32_t k = late_klo; k < late_khi; ++k) {
+                    if (w == 0) { run = 0; first_reset = first_reset < k ? first_reset : k; }
+                    run += my[k];
+                    my[k] = run;
+                    w = (w + 1 == W) ? 0u : w + 1;
+                }
+                my_tail = run;
+                my_reset = first_reset;
             }
+        }
+        {
+            // ---- carries: what each lane's leading elements (before its first row start) lack ----
+            int32_t v = my_tail;                                        // 0 in lanes without a sub-block
+            uint32_t f = (lane < (int)nsb && my_reset != (uint32_t)SUB) ? 1u : 0u;   // the lane's run contains a row start
+            wave_segmented_sum(v, f);                                   // v: row-sum at the end of the lane's run
+            // what flows into a lane is the inclusive value of the lane before it; a band begins a row
+            int32_t into = (int32_t)dpp_u32<0x138, 0xf>((uint32_t)v);   // wave_shr:1
+            if (lane == 0) into = 0;
+            if (lane < kND) RC[lane] = make_uint2(lane < (int)nsb ? my_reset : 0u, (uint32_t)into);
         }
         wave_sync();
 
