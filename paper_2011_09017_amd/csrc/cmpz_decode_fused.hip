@@ -9,8 +9,10 @@
 // ALU latency), another runs its column pass (stores) and a third waits for
 // its next payload.  The four waves of a workgroup share only the tables.
 // Planes larger than a band are walked band by band with running column sums
-// (needs W <= 256).  Shapes that fit neither case take the unfused kernels of
-// cmpz_decompress.hip.
+// (needs W <= 256); where a tensor has few such planes, a variant of the kernel
+// gives a plane to a workgroup, whose waves decode four bands side by side and
+// share the column pass by columns.  Shapes that fit neither case take the
+// unfused kernels of cmpz_decompress.hip.
 //
 // A band is decoded by one lane per sub-block (the container stores each
 // sub-block's bit count, so every lane knows where its codes start) into an LDS
@@ -23,7 +25,7 @@
 // straight from memory instead).  In a band without outliers a lane adds up its
 // residuals along the row while it decodes them, so what it stores is already the
 // row prefix sum up to a per-lane carry; one segmented scan over the lanes'
-// totals yields the carries, and the column pass (one lane per column, eight
+// totals yields the carries, and the column pass (one lane per column, four
 // rows in flight) adds them on the fly, de-quantises and stores.  A band with
 // outliers stores plain residuals and patches the outliers in; then its lanes
 // sum their rows in LDS, and the rest is the same.
