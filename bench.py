@@ -63,8 +63,8 @@ MEASURED_TRAFFIC = {
         "per_elem": {
             "k_quant_lorenzo_split_hist": 4.0178 + 1.0509,     # 8-bit symbols in the scratch
             "k_lengths": 1.0088 + 0.0672,
-            "k_pack": 1.0146 + 0.6639,
-            "k_decode_fused": 0.8339 + 4.0086,
+            "k_pack": 1.0138 + 0.6639,
+            "k_decode_fused": 0.8330 + 4.0086,
         },
     },
 }
