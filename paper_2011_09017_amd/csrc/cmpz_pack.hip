@@ -302,7 +302,7 @@ constexpr uint32_t kImageUnits = kStepBitsMax / 128 + 2;               // the op
 constexpr uint32_t kImageWords = kImageUnits * 4;
 
 template <bool ZB>
-__global__ __launch_bounds__(kThreads, ZB ? 4 : 6) void k_pack(BatchC b)
+__global__ __launch_bounds__(kThreads, ZB ? 5 : 6) void k_pack(BatchC b)
 {
     __shared__ uint64_t table[kMaxSym + 1];          // length << 56 | code; or, as 32-bit words, code << (32 - length) | length
     __shared__ __align__(16) uint32_t images[kWaves][kImageWords];
