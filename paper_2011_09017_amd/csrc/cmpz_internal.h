@@ -237,8 +237,8 @@ __host__ __device__ inline DecompressArgs decompress_args(const BatchD &b, const
     return a;
 }
 
-constexpr uint32_t kLB = 11;                      // bits resolved by the first decode table (8 KB of LDS; with the
-                                                  // fused decoder's other arrays four workgroups just fit a CU)
+constexpr uint32_t kLB = 11;                      // bits resolved by the first decode table (4 KB of LDS; with the
+                                                  // fused decoder's other arrays five workgroups just fit a CU)
 struct DecodeTables;                              // cmpz_decode_core.h
 
 // Pre-quantisation of one value (Section 3.1, first stage): one fp32 multiply, clamp to +-16384
