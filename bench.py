@@ -66,8 +66,17 @@ MEASURED_TRAFFIC = {
             "k_pack": 1.0138 + 0.6639,
             "k_decode_fused": 0.8330 + 4.0086,
         },
+        # vector instructions per element and the fraction of the kernel's time its vector units are busy
+        # (profiles/instruction_counters_cfg5_resnet18_stream.txt)
+        "valu": {
+            "k_quant_lorenzo_split_hist": (26.48, 0.688),
+            "k_lengths": (2.98, 0.355),
+            "k_pack": (12.27, 0.831),
+            "k_decode_fused": (46.83, 0.829),
+        },
     },
 }
+ALU_PEAK_LANE_INST_PER_S = 256 * 4 * 16 * 2.4e9       # CUs x SIMDs x lanes x clock: 39.3 T lane-instructions/s
 
 
 class Run:
@@ -308,6 +317,12 @@ def main() -> int:
                     "alg_bytes_per_elem": round(bytes_fn(cbar), 4),
                     "avg_launch_us": round(kern[dom]["avg_us"], 2),
                     "launches_per_step": kern[dom]["launches_per_step"]}
+        valu = meas.get("valu", {}).get(dom)
+        if valu:
+            # context, not the bound reported: what the kernel's vector instructions alone would take
+            roofline["alu"] = {"valu_inst_per_elem": valu[0], "valu_busy": valu[1],
+                               "floor_us": round(valu[0] * total / kern[dom]["launches_per_step"] / ALU_PEAK_LANE_INST_PER_S * 1e6, 1),
+                               "source": "profiles/instruction_counters_cfg5_resnet18_stream.txt"}
 
     # what a plain device copy of the largest tensor reaches on this machine (bytes read + written)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
